@@ -1,0 +1,135 @@
+/*
+ * jet.h -- C ABI of libjet: the block-scaled FP8 linear layer of Jet-RL's
+ * unified precision flow, for AMD MI355X (gfx950).
+ *
+ * One linear layer Y = X W^T (Jet-RL, Sec. 2.2) runs three GEMMs -- FProp,
+ * DGrad, WGrad -- on FP8 E4M3 operands (Sec. 2.1: Delta_max = 448) quantized
+ * with 1x128 groups for activations and gradients and 128x128 blocks for
+ * weights (Sec. 4.2).  Rollout (decode-shaped, small M) and training forward
+ * call the SAME entry point and obtain bit-identical rows (Sec. 4.1: the
+ * inference graph is a subgraph of the training forward graph).
+ *
+ * Conventions for every call
+ *   - M = tokens, N = output features, K = input features (the paper's N, D, C).
+ *   - Every pointer is a DEVICE pointer to a dense row-major array owned by the
+ *     caller; the library allocates nothing, keeps no pointer after the call
+ *     returns, and does not synchronise.  Required pointers must be 16-byte
+ *     aligned.  Outputs must not alias inputs.
+ *   - bf16 arrays are passed as void* (2 bytes per element); FP8 arrays are
+ *     uint8_t E4M3 codes; scales are IEEE binary32.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream);
+ *     work is enqueued asynchronously on it.
+ *   - Errors are return codes only.  All argument checks happen on the host
+ *     before anything is launched; on error nothing is written.
+ *   - Inputs must be finite (NaN / Inf: no fault, result unspecified).
+ *   - Same inputs give the same bytes on every call; kernel selection depends
+ *     on shapes only and does not change any output bit.
+ *
+ * Quantizer (Sec. 2.1):  S = max|X| / 448 over the group (binary32 division;
+ * S = 1 for an all-zero group),  code = E4M3( X / S ) rounded to nearest, ties
+ * to even, saturating at +-448, sign of zero kept.
+ *
+ * GEMM element (Sec. 2.2 on Sec. 4.2 operands), R = reduction length:
+ *   acc = 0;  for g = 0 .. R/128-1 ascending:
+ *       p   = sum over the 128 products of group g  (FP8 matrix-core sum)
+ *       s   = sa[i,g] * sb[.,g]                     (binary32 product)
+ *       acc = fma(p, s, acc)                        (binary32)
+ *   out = bf16(acc), round to nearest even.
+ * The chain is the same for every M, so a token row does not depend on the
+ * call it is computed in.
+ */
+#ifndef JET_H
+#define JET_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    JET_OK = 0,
+    JET_ERR_NULL = 1,   /* a required pointer is NULL */
+    JET_ERR_SHAPE = 2,  /* a size is < 1 or breaks a divisibility rule */
+    JET_ERR_ALIGN = 3,  /* a pointer is not 16-byte aligned */
+    JET_ERR_ARG = 4,    /* bad enum value or inconsistent optional arguments */
+    JET_ERR_LAUNCH = 5  /* the HIP runtime refused the launch */
+} jet_status;
+
+/* Source format of jet_quant_act. */
+typedef enum {
+    JET_SRC_BF16 = 0,    /* x is bf16 [M,K] */
+    JET_SRC_FP8_ROW = 1  /* x is E4M3 [M,K] with x_scales f32 [M,K/128]; the element
+                            value is decode(code) * scale (one binary32 multiply):
+                            the FP8-saved activation of Sec. 4.1 */
+} jet_src;
+
+/*
+ * 1x128 per-group quantization of activations and gradients (Sec. 4.2).
+ * One pass over x emits either or both of
+ *   row  : groups of 128 consecutive k of one row m
+ *          q_row  u8 [M,K],  s_row  f32 [M,K/128]      needs K % 128 == 0
+ *   colT : groups of 128 consecutive m of one column k, stored transposed
+ *          q_colT u8 [K,M],  s_colT f32 [K,M/128]      needs M % 128 == 0
+ * (the 128x1 operand of WGrad; both at once is the fused quantization of dY
+ * for DGrad and WGrad).  A pair is skipped when both its pointers are NULL;
+ * giving only one pointer of a pair is JET_ERR_NULL; skipping both pairs is
+ * JET_ERR_ARG.  x_scales is required for JET_SRC_FP8_ROW (else ignored).
+ */
+jet_status jet_quant_act(const void* x, const float* x_scales, jet_src src,
+                         int64_t M, int64_t K,
+                         uint8_t* q_row, float* s_row,
+                         uint8_t* q_colT, float* s_colT,
+                         void* stream);
+
+/*
+ * 128x128 per-block quantization of weights (Sec. 4.2).  w bf16 [N,K] ->
+ * q u8 [N,K], s f32 [N/128,K/128].  Optional transposed copy for DGrad:
+ * qT u8 [K,N], sT f32 [K/128,N/128] with the same codes and scales (the scheme
+ * is symmetric under transpose).  qT and sT are given together or both NULL.
+ * Needs N % 128 == 0 and K % 128 == 0.
+ */
+jet_status jet_quant_weight(const void* w, int64_t N, int64_t K,
+                            uint8_t* q, float* s, uint8_t* qT, float* sT,
+                            void* stream);
+
+/*
+ * FProp (Sec. 2.2):  y bf16 [M,N] = X W^T  from (qx,sx) = row quantization of
+ * X [M,K] and (qw,sw) = block quantization of W [N,K].  Any M >= 1 (decode and
+ * training shapes alike); N % 128 == 0, K % 128 == 0.
+ */
+jet_status jet_fp8_linear_fwd(const uint8_t* qx, const float* sx,
+                              const uint8_t* qw, const float* sw,
+                              void* y, int64_t M, int64_t N, int64_t K,
+                              void* stream);
+
+/*
+ * DGrad (Sec. 2.2):  dx bf16 [M,K] = dY W  from (qdy,sdy) = row quantization
+ * of dY [M,N] (groups along N) and (qwT,swT) = the transposed copy written by
+ * jet_quant_weight ([K,N], [K/128,N/128]).  Any M >= 1; N, K multiples of 128.
+ */
+jet_status jet_fp8_linear_dgrad(const uint8_t* qdy, const float* sdy,
+                                const uint8_t* qwT, const float* swT,
+                                void* dx, int64_t M, int64_t N, int64_t K,
+                                void* stream);
+
+/*
+ * WGrad (Sec. 2.2):  dw bf16 [N,K] = dY^T X  from the column-transposed
+ * quantizations (qdyT,sdyT) [N,M],[N,M/128] and (qxT,sxT) [K,M],[K,M/128],
+ * both grouped along the token axis.  M, N, K multiples of 128.
+ */
+jet_status jet_fp8_linear_wgrad(const uint8_t* qdyT, const float* sdyT,
+                                const uint8_t* qxT, const float* sxT,
+                                void* dw, int64_t M, int64_t N, int64_t K,
+                                void* stream);
+
+/* Text for a status code (static storage). */
+const char* jet_status_str(jet_status st);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int jet_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* JET_H */

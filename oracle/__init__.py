@@ -61,7 +61,7 @@ def lib() -> ctypes.CDLL:
         L.orc_quant_weight.restype = i32
         L.orc_quant_weight.argtypes = [vp, i64, i64, vp, vp, vp, vp]
         L.orc_gemm.restype = i32
-        L.orc_gemm.argtypes = [vp, vp, vp, vp, i32, i64, i64, i64, vp, i64, vp, i64, vp, vp, vp, vp]
+        L.orc_gemm.argtypes = [vp, vp, vp, vp, i32, i64, i64, i64, vp, i64, vp, i64, vp, vp, vp, vp, vp]
         for name in ("orc_fp8_linear_fwd", "orc_fp8_linear_dgrad", "orc_fp8_linear_wgrad"):
             f = getattr(L, name)
             f.restype = i32
@@ -160,8 +160,9 @@ def gemm(a, sa, b, sb, sb_mode=SB_BLOCK, rows=None, cols=None, want_exact=True):
     """OUT[i,j] = sum_r A[i,r] B[j,r] on block-scaled FP8 operands.
 
     Returns dict(acc=f32 reference-order result, out=bf16 bits, exact=f64
-    order-independent value, sum_abs=f64 sum of |group terms|), compact over the
-    requested rows / cols."""
+    order-independent value, sum_abs=f64 sum of |group terms|, sum_abs_prod=f64
+    sum of |single products| times the group scales), compact over the requested
+    rows / cols."""
     a, b = _c(a, np.uint8), _c(b, np.uint8)
     sa, sb = _c(sa, np.float32), _c(sb, np.float32)
     I, R = a.shape
@@ -176,9 +177,10 @@ def gemm(a, sa, b, sb, sb_mode=SB_BLOCK, rows=None, cols=None, want_exact=True):
     out = np.empty((nr, nc), np.uint16)
     exact = np.empty((nr, nc), np.float64) if want_exact else None
     sabs = np.empty((nr, nc), np.float64) if want_exact else None
+    sprod = np.empty((nr, nc), np.float64) if want_exact else None
     _check(lib().orc_gemm(_p(a), _p(sa), _p(b), _p(sb), sb_mode, I, J, R, _p(r), nr, _p(c), nc,
-                          _p(acc), _p(out), _p(exact), _p(sabs)))
-    return {"acc": acc, "out": out, "exact": exact, "sum_abs": sabs}
+                          _p(acc), _p(out), _p(exact), _p(sabs), _p(sprod)))
+    return {"acc": acc, "out": out, "exact": exact, "sum_abs": sabs, "sum_abs_prod": sprod}
 
 
 def _named(fn, a, sa, b, sb, M, N, K, oshape):

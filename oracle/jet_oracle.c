@@ -25,6 +25,7 @@
 #include <stdint.h>
 #include <string.h>
 #include <stddef.h>
+#include <stdlib.h>
 
 #ifdef _OPENMP
 #include <omp.h>
@@ -266,7 +267,8 @@ int orc_quant_weight(const uint16_t* w, int64_t N, int64_t K, uint8_t* q, float*
  *
  * Exact companion: the group sum as an integer in units of 2^-18 (every E4M3
  * value is a multiple of 2^-9), times s, summed over groups in long double.
- * sum_abs = sum_g |s_g * p_g(exact)| measures cancellation. */
+ * sum_abs = sum_g |s_g * p_g(exact)| measures cancellation across groups,
+ * sum_abs_prod = sum_g s_g * sum_r |a_r b_r| cancellation down to single products. */
 /* decode(b) for all 256 codes, filled from orc_e4m3_decode (a lookup of the
  * definition, so that sampled checks at the large shapes finish in seconds);
  * TABI holds the same values as integers in units of 2^-9. */
@@ -281,29 +283,33 @@ static void fill_tables(void) {
 }
 
 static void gemm_elem(const uint8_t* a, const float* sa, const uint8_t* b, const float* sb,
-                      int64_t R, float* acc_out, double* exact_out, double* sum_abs_out) {
+                      int64_t R, float* acc_out, double* exact_out, double* sum_abs_out,
+                      double* sum_abs_prod_out) {
     int64_t G = R / GROUP;
     float acc = 0.0f;
-    long double ex = 0.0L, sabs = 0.0L;
+    long double ex = 0.0L, sabs = 0.0L, sprod = 0.0L;
     for (int64_t g = 0; g < G; ++g) {
         volatile float p = 0.0f;
-        int64_t pi = 0;
+        int64_t pi = 0, pa = 0;
         for (int64_t r = g * GROUP; r < (g + 1) * GROUP; ++r) {
             float va = TAB[a[r]];
             float vb = TAB[b[r]];
             volatile float prod = va * vb; /* exact: two 4-bit significands */
             p = p + prod;
             pi += (int64_t)TABI[a[r]] * (int64_t)TABI[b[r]];
+            pa += llabs((int64_t)TABI[a[r]] * (int64_t)TABI[b[r]]);
         }
         volatile float s = sa[g] * sb[g];
         acc = fmaf(p, s, acc);
         long double term = (long double)s * ldexpl((long double)pi, -18);
         ex += term;
         sabs += fabsl(term);
+        sprod += fabsl((long double)s) * ldexpl((long double)pa, -18);
     }
     *acc_out = acc;
     if (exact_out) *exact_out = (double)ex;
     if (sum_abs_out) *sum_abs_out = (double)sabs;
+    if (sum_abs_prod_out) *sum_abs_prod_out = (double)sprod;
 }
 
 /* Sampled / full GEMM.  a u8 [I,R], sa f32 [I,R/128]; b u8 [J,R];
@@ -311,11 +317,12 @@ static void gemm_elem(const uint8_t* a, const float* sa, const uint8_t* b, const
  * rows / cols: index lists into I / J, or NULL for all of them.
  * Outputs (each may be NULL), compact [nrows, ncols] row-major:
  *   acc  binary32 reference-order result      out_bf16  its bf16 rounding
- *   exact  order-independent value (double)   sum_abs   sum_g |s_g p_g|     */
+ *   exact  order-independent value (double)   sum_abs   sum_g |s_g p_g|
+ *   sum_abs_prod  sum_g s_g sum_r |a_r b_r|                                  */
 int orc_gemm(const uint8_t* a, const float* sa, const uint8_t* b, const float* sb, int sb_mode,
              int64_t I, int64_t J, int64_t R, const int64_t* rows, int64_t nrows,
              const int64_t* cols, int64_t ncols, float* acc, uint16_t* out_bf16, double* exact,
-             double* sum_abs) {
+             double* sum_abs, double* sum_abs_prod) {
     if (!a || !sa || !b || !sb) return ORC_ERR_NULL;
     if (I < 1 || J < 1 || R < 1 || R % GROUP) return ORC_ERR_SHAPE;
     if (sb_mode == ORC_SB_BLOCK && J % GROUP) return ORC_ERR_SHAPE;
@@ -335,13 +342,14 @@ int orc_gemm(const uint8_t* a, const float* sa, const uint8_t* b, const float* s
             int64_t j = cols ? cols[jj] : jj;
             const float* sbp = (sb_mode == ORC_SB_BLOCK) ? sb + (j / GROUP) * G : sb + j * G;
             float v;
-            double e, sa_abs;
-            gemm_elem(a + i * R, sa + i * G, b + j * R, sbp, R, &v, &e, &sa_abs);
+            double e, sa_abs, sa_prod;
+            gemm_elem(a + i * R, sa + i * G, b + j * R, sbp, R, &v, &e, &sa_abs, &sa_prod);
             int64_t o = ii * ncols + jj;
             if (acc) acc[o] = v;
             if (out_bf16) out_bf16[o] = orc_bf16_rne(v);
             if (exact) exact[o] = e;
             if (sum_abs) sum_abs[o] = sa_abs;
+            if (sum_abs_prod) sum_abs_prod[o] = sa_prod;
         }
     }
     return ORC_OK;
@@ -350,7 +358,7 @@ int orc_gemm(const uint8_t* a, const float* sa, const uint8_t* b, const float* s
 /* FProp  Y[M,N] = X W^T :  (qx,sx)[M,K] 1x128 along K,  (qw,sw)[N,K] 128x128. */
 int orc_fp8_linear_fwd(const uint8_t* qx, const float* sx, const uint8_t* qw, const float* sw,
                        int64_t M, int64_t N, int64_t K, float* acc, uint16_t* y) {
-    return orc_gemm(qx, sx, qw, sw, ORC_SB_BLOCK, M, N, K, NULL, 0, NULL, 0, acc, y, NULL, NULL);
+    return orc_gemm(qx, sx, qw, sw, ORC_SB_BLOCK, M, N, K, NULL, 0, NULL, 0, acc, y, NULL, NULL, NULL);
 }
 
 /* DGrad  dX[M,K] = dY W :  (qdy,sdy)[M,N] 1x128 along N,  (qwT,swT)[K,N] 128x128. */
@@ -358,7 +366,7 @@ int orc_fp8_linear_dgrad(const uint8_t* qdy, const float* sdy, const uint8_t* qw
                          const float* swT, int64_t M, int64_t N, int64_t K, float* acc,
                          uint16_t* dx) {
     return orc_gemm(qdy, sdy, qwT, swT, ORC_SB_BLOCK, M, K, N, NULL, 0, NULL, 0, acc, dx, NULL,
-                    NULL);
+                    NULL, NULL);
 }
 
 /* WGrad  dW[N,K] = dY^T X :  (qdyT,sdyT)[N,M] and (qxT,sxT)[K,M], both in
@@ -367,7 +375,7 @@ int orc_fp8_linear_wgrad(const uint8_t* qdyT, const float* sdyT, const uint8_t* 
                          const float* sxT, int64_t M, int64_t N, int64_t K, float* acc,
                          uint16_t* dw) {
     return orc_gemm(qdyT, sdyT, qxT, sxT, ORC_SB_ROW, N, K, M, NULL, 0, NULL, 0, acc, dw, NULL,
-                    NULL);
+                    NULL, NULL);
 }
 
 /* vector helpers for the tests */

@@ -1,0 +1,175 @@
+"""ctypes binding of libjet.so: argument marshalling only.
+
+``jet_*`` functions mirror include/jet.h one to one (raw pointers, sizes, a
+stream handle; they return the status code).  The un-prefixed helpers take
+torch CUDA tensors, allocate the outputs with torch, pass ``data_ptr()`` and the
+current stream, and raise ``JetError`` on a non-zero status.  No arithmetic of
+the method happens in Python, and there is no fallback: if libjet.so is missing
+the import of the library fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libjet.so")
+
+JET_SRC_BF16 = 0
+JET_SRC_FP8_ROW = 1
+GROUP = 128
+
+_lib = None
+
+
+class JetError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: jet_status {status} ({jet_status_str(status)})")
+
+
+def lib() -> ctypes.CDLL:
+    """Load libjet.so (built in-tree by paper_2601_14243_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2601_14243_amd.build` "
+                "(there is no CPU or PyTorch fallback)")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        L.jet_quant_act.restype = i32
+        L.jet_quant_act.argtypes = [vp, vp, i32, i64, i64, vp, vp, vp, vp, vp]
+        L.jet_quant_weight.restype = i32
+        L.jet_quant_weight.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp]
+        for name in ("jet_fp8_linear_fwd", "jet_fp8_linear_dgrad", "jet_fp8_linear_wgrad"):
+            f = getattr(L, name)
+            f.restype = i32
+            f.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp]
+        L.jet_status_str.restype = ctypes.c_char_p
+        L.jet_status_str.argtypes = [i32]
+        L.jet_version.restype = i32
+        _lib = L
+    return _lib
+
+
+# ---------------------------------------------------------------- raw calls
+
+def jet_version() -> int:
+    return int(lib().jet_version())
+
+
+def jet_status_str(status: int) -> str:
+    return lib().jet_status_str(int(status)).decode()
+
+
+def jet_quant_act(x, x_scales, src, M, K, q_row, s_row, q_colT, s_colT, stream) -> int:
+    return int(lib().jet_quant_act(x, x_scales, src, M, K, q_row, s_row, q_colT, s_colT, stream))
+
+
+def jet_quant_weight(w, N, K, q, s, qT, sT, stream) -> int:
+    return int(lib().jet_quant_weight(w, N, K, q, s, qT, sT, stream))
+
+
+def jet_fp8_linear_fwd(qx, sx, qw, sw, y, M, N, K, stream) -> int:
+    return int(lib().jet_fp8_linear_fwd(qx, sx, qw, sw, y, M, N, K, stream))
+
+
+def jet_fp8_linear_dgrad(qdy, sdy, qwT, swT, dx, M, N, K, stream) -> int:
+    return int(lib().jet_fp8_linear_dgrad(qdy, sdy, qwT, swT, dx, M, N, K, stream))
+
+
+def jet_fp8_linear_wgrad(qdyT, sdyT, qxT, sxT, dw, M, N, K, stream) -> int:
+    return int(lib().jet_fp8_linear_wgrad(qdyT, sdyT, qxT, sxT, dw, M, N, K, stream))
+
+
+# ------------------------------------------------------- tensor conveniences
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _need(t: torch.Tensor, dtype, name: str):
+    if not t.is_cuda or not t.is_contiguous() or t.dtype != dtype or t.dim() != 2:
+        raise TypeError(f"{name}: need a contiguous 2-D CUDA tensor of {dtype}")
+
+
+def quant_act(x: torch.Tensor, x_scales: torch.Tensor | None = None, row: bool = True,
+              col: bool = False, out: dict | None = None) -> dict:
+    """1x128 quantization of a bf16 [M,K] tensor, or of an FP8-saved one (uint8 codes
+    plus x_scales).  Returns dict(q_row, s_row, q_colT, s_colT) with the requested pairs."""
+    src = JET_SRC_BF16 if x_scales is None else JET_SRC_FP8_ROW
+    _need(x, torch.bfloat16 if src == JET_SRC_BF16 else torch.uint8, "x")
+    M, K = x.shape
+    dev = x.device
+    o = {} if out is None else out
+    if row and "q_row" not in o:
+        o["q_row"] = torch.empty((M, K), dtype=torch.uint8, device=dev)
+        o["s_row"] = torch.empty((M, max(K // GROUP, 1)), dtype=torch.float32, device=dev)
+    if col and "q_colT" not in o:
+        o["q_colT"] = torch.empty((K, M), dtype=torch.uint8, device=dev)
+        o["s_colT"] = torch.empty((K, max(M // GROUP, 1)), dtype=torch.float32, device=dev)
+    st = jet_quant_act(_ptr(x), _ptr(x_scales), src, M, K,
+                       _ptr(o.get("q_row")) if row else None, _ptr(o.get("s_row")) if row else None,
+                       _ptr(o.get("q_colT")) if col else None, _ptr(o.get("s_colT")) if col else None,
+                       _stream())
+    if st:
+        raise JetError(st, "jet_quant_act")
+    return o
+
+
+def quant_weight(w: torch.Tensor, transposed: bool = False, out: tuple | None = None):
+    """128x128 quantization of bf16 [N,K].  Returns (q, s) or (q, s, qT, sT)."""
+    _need(w, torch.bfloat16, "w")
+    N, K = w.shape
+    dev = w.device
+    if out is None:
+        q = torch.empty((N, K), dtype=torch.uint8, device=dev)
+        s = torch.empty((max(N // GROUP, 1), max(K // GROUP, 1)), dtype=torch.float32, device=dev)
+        qT = torch.empty((K, N), dtype=torch.uint8, device=dev) if transposed else None
+        sT = torch.empty((max(K // GROUP, 1), max(N // GROUP, 1)), dtype=torch.float32, device=dev) if transposed else None
+    else:
+        q, s, qT, sT = (tuple(out) + (None, None))[:4]
+    st = jet_quant_weight(_ptr(w), N, K, _ptr(q), _ptr(s), _ptr(qT), _ptr(sT), _stream())
+    if st:
+        raise JetError(st, "jet_quant_weight")
+    return (q, s, qT, sT) if transposed else (q, s)
+
+
+def fp8_linear_fwd(qx, sx, qw, sw, out: torch.Tensor | None = None) -> torch.Tensor:
+    """y bf16 [M,N] = X W^T."""
+    M, K = qx.shape
+    N = qw.shape[0]
+    y = torch.empty((M, N), dtype=torch.bfloat16, device=qx.device) if out is None else out
+    st = jet_fp8_linear_fwd(_ptr(qx), _ptr(sx), _ptr(qw), _ptr(sw), _ptr(y), M, N, K, _stream())
+    if st:
+        raise JetError(st, "jet_fp8_linear_fwd")
+    return y
+
+
+def fp8_linear_dgrad(qdy, sdy, qwT, swT, out: torch.Tensor | None = None) -> torch.Tensor:
+    """dx bf16 [M,K] = dY W."""
+    M, N = qdy.shape
+    K = qwT.shape[0]
+    dx = torch.empty((M, K), dtype=torch.bfloat16, device=qdy.device) if out is None else out
+    st = jet_fp8_linear_dgrad(_ptr(qdy), _ptr(sdy), _ptr(qwT), _ptr(swT), _ptr(dx), M, N, K, _stream())
+    if st:
+        raise JetError(st, "jet_fp8_linear_dgrad")
+    return dx
+
+
+def fp8_linear_wgrad(qdyT, sdyT, qxT, sxT, out: torch.Tensor | None = None) -> torch.Tensor:
+    """dw bf16 [N,K] = dY^T X."""
+    N, M = qdyT.shape
+    K = qxT.shape[0]
+    dw = torch.empty((N, K), dtype=torch.bfloat16, device=qdyT.device) if out is None else out
+    st = jet_fp8_linear_wgrad(_ptr(qdyT), _ptr(sdyT), _ptr(qxT), _ptr(sxT), _ptr(dw), M, N, K, _stream())
+    if st:
+        raise JetError(st, "jet_fp8_linear_wgrad")
+    return dw

@@ -1,0 +1,81 @@
+"""Shared helpers of the GPU parity tests: host<->device moves and the GEMM
+acceptance rule.  The oracle (CPU) and libjet (GPU) meet only here, on seeded
+inputs from jet_inputs."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+DEV = "cuda:0"
+
+
+def dev_bf16(bits: np.ndarray) -> torch.Tensor:
+    """uint16 bf16 bit patterns -> bf16 tensor on the GPU (no value conversion)."""
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).to(DEV)
+
+
+def dev(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def host_bits(t: torch.Tensor) -> np.ndarray:
+    """bf16 GPU tensor -> uint16 bit patterns on the host."""
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def host(t: torch.Tensor) -> np.ndarray:
+    return t.cpu().numpy()
+
+
+def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def ulp_bf16(v: np.ndarray) -> np.ndarray:
+    """Spacing of bf16 at |v| (8 significant bits), floored at the smallest normal binade."""
+    a = np.abs(np.asarray(v, np.float64))
+    e = np.floor(np.log2(np.maximum(a, 2.0 ** -126)))
+    return 2.0 ** (e - 7)
+
+
+# Allowance for the matrix core's in-instruction accumulation: inside one 16x16x128 FP8
+# MFMA the products of a small block are aligned to the block's largest exponent and cut
+# to about 14 bits before they are added (measured on gfx950: adding 2^j next to +-2^16 is
+# kept for j >= 3 only), so a group sum deviates from the exact sum by a few 2^-20 of
+# sum|a_r b_r| on average and less than 2^-14 of it always.
+HW_ACCUM_REL = 2.0 ** -14
+
+
+def check_gemm(y_bits: np.ndarray, ref: dict, what: str, min_strict: float = 0.995) -> dict:
+    """Acceptance of a GPU GEMM output against the oracle.
+
+    (i)  strict: |y - acc| <= 2 ulp_bf16(acc) against the oracle's fp32 reference-order
+         result; must hold for at least `min_strict` of the elements, and every element
+         that misses it must be a cancellation case (|acc| < 2^-6 sum|products|);
+    (ii) every element: |y - exact| <= 2 ulp_bf16(exact) + HW_ACCUM_REL * sum|s a b|.
+    Returns the statistics (also useful to report)."""
+    y = bf16_bits_to_f64(y_bits)
+    acc = ref["acc"].astype(np.float64)
+    exact, T = ref["exact"], ref["sum_abs_prod"]
+    err_acc = np.abs(y - acc)
+    strict_ok = err_acc <= 2.0 * ulp_bf16(acc)
+    frac = float(strict_ok.mean())
+    err_ex = np.abs(y - exact)
+    tol = 2.0 * ulp_bf16(exact) + HW_ACCUM_REL * T
+    worst = float(np.max(err_ex / tol))
+    bad_strict = ~strict_ok
+    stats = {
+        "what": what, "n": int(y.size), "strict_frac": frac,
+        "strict_fail": int(bad_strict.sum()),
+        "worst_strict_ulps": float(np.max(err_acc / ulp_bf16(acc))),
+        "worst_vs_tol": worst,
+        "max_err_over_T": float(np.max((err_ex - 0.5 * ulp_bf16(exact)).clip(min=0) / np.maximum(T, 1e-300))),
+        "exact_match_frac": float((y_bits == ref["out"]).mean()),
+    }
+    print("GEMM parity", stats)
+    assert np.all(err_ex <= tol), f"{what}: element beyond the documented tolerance: {stats}"
+    assert frac >= min_strict, f"{what}: strict 2-ulp pass fraction too low: {stats}"
+    if bad_strict.any():
+        assert np.all(np.abs(acc[bad_strict]) < 2.0 ** -6 * T[bad_strict]), \
+            f"{what}: a strict miss that is not a cancellation case: {stats}"
+    return stats

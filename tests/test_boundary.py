@@ -1,0 +1,82 @@
+"""The C-ABI boundary without a GPU: libjet.so loads, exports every symbol that
+include/jet.h declares, and rejects bad arguments on the host before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "jet.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2601_14243_amd import binding
+    return binding.lib()
+
+
+def _declared():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(jet_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_header_symbols_are_exported(L):
+    names = _declared()
+    assert {"jet_quant_act", "jet_quant_weight", "jet_fp8_linear_fwd", "jet_fp8_linear_dgrad",
+            "jet_fp8_linear_wgrad", "jet_status_str", "jet_version"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_version_and_status_text(L):
+    from paper_2601_14243_amd import binding
+    assert binding.jet_version() >= 100
+    assert binding.jet_status_str(0) == "ok"
+    texts = {binding.jet_status_str(i) for i in range(6)}
+    assert len(texts) == 6
+
+
+A = 0x1000          # a fake, 16-byte aligned, never dereferenced device address
+OK, NULL, SHAPE, ALIGN, ARG = 0, 1, 2, 3, 4
+
+
+def test_quant_act_argument_errors(L):
+    from paper_2601_14243_amd import binding as b
+    assert b.jet_quant_act(None, None, 0, 128, 128, A, A, None, None, None) == NULL
+    assert b.jet_quant_act(A, None, 7, 128, 128, A, A, None, None, None) == ARG
+    assert b.jet_quant_act(A, None, 1, 128, 128, A, A, None, None, None) == ARG      # FP8 source without scales
+    assert b.jet_quant_act(A, None, 0, 128, 128, None, None, None, None, None) == ARG  # no output pair
+    assert b.jet_quant_act(A, None, 0, 128, 128, A, None, None, None, None) == NULL   # half a pair
+    assert b.jet_quant_act(A, None, 0, 128, 128, None, None, None, A, None) == NULL
+    assert b.jet_quant_act(A, None, 0, 0, 128, A, A, None, None, None) == SHAPE
+    assert b.jet_quant_act(A, None, 0, 4, 100, A, A, None, None, None) == SHAPE       # K % 128
+    assert b.jet_quant_act(A, None, 0, 100, 128, None, None, A, A, None) == SHAPE     # M % 128 in column mode
+    assert b.jet_quant_act(A + 4, None, 0, 4, 128, A, A, None, None, None) == ALIGN
+    assert b.jet_quant_act(A, None, 0, 4, 128, A, A + 8, None, None, None) == ALIGN
+
+
+def test_quant_weight_argument_errors(L):
+    from paper_2601_14243_amd import binding as b
+    assert b.jet_quant_weight(None, 128, 128, A, A, None, None, None) == NULL
+    assert b.jet_quant_weight(A, 128, 128, A, None, None, None, None) == NULL
+    assert b.jet_quant_weight(A, 128, 128, A, A, A, None, None) == ARG                # qT without sT
+    assert b.jet_quant_weight(A, 100, 128, A, A, None, None, None) == SHAPE
+    assert b.jet_quant_weight(A, 128, -128, A, A, None, None, None) == SHAPE
+    assert b.jet_quant_weight(A, 128, 128, A + 2, A, None, None, None) == ALIGN
+
+
+@pytest.mark.parametrize("fn", ["jet_fp8_linear_fwd", "jet_fp8_linear_dgrad", "jet_fp8_linear_wgrad"])
+def test_gemm_argument_errors(L, fn):
+    from paper_2601_14243_amd import binding as b
+    f = getattr(b, fn)
+    assert f(None, A, A, A, A, 128, 128, 128, None) == NULL
+    assert f(A, A, A, A, None, 128, 128, 128, None) == NULL
+    assert f(A, A, A, A, A, 0, 128, 128, None) == SHAPE
+    assert f(A, A, A, A, A, 128, 100, 128, None) == SHAPE
+    assert f(A, A, A, A, A, 128, 128, 200, None) == SHAPE
+    assert f(A, A + 1, A, A, A, 128, 128, 128, None) == ALIGN
+    want = SHAPE if fn == "jet_fp8_linear_wgrad" else None
+    if want is not None:
+        assert f(A, A, A, A, A, 100, 128, 128, None) == want                         # WGrad needs M % 128

@@ -1,0 +1,162 @@
+"""GPU parity of the three FP8 GEMMs (Sec. 2.2) against the oracle, and the
+row-level invariance between decode-shaped and training-shaped calls (Sec. 4.1)."""
+import numpy as np
+import pytest
+import torch
+
+import jet_inputs as ji
+import oracle as orc
+from jet_testlib import check_gemm, dev, dev_bf16, host, host_bits
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def jet():
+    import paper_2601_14243_amd as j
+    assert torch.cuda.is_available()
+    j.lib()
+    return j
+
+
+def _fwd_case(jet, M, N, K, seed):
+    x, w = ji.activations(M, K, seed), ji.weights(N, K, seed + 1)
+    qa = orc.quant_act(x)
+    qw, sw = orc.quant_weight(w)
+    ref = orc.gemm(qa["q_row"], qa["s_row"], qw, sw)
+    y = jet.fp8_linear_fwd(dev(qa["q_row"]), dev(qa["s_row"]), dev(qw), dev(sw))
+    torch.cuda.synchronize()
+    return host_bits(y), ref
+
+
+def test_config0_forward_end_to_end(jet):
+    """Config 0 in full: X [256,1024] with outlier channels, W [1024,1024]; quantizers
+    and GEMM all on the GPU, compared with the oracle run on the same bf16 inputs."""
+    M, N, K = 256, 1024, 1024
+    x = ji.activations(M, K, ji.seed_for(0, 0, ji.TENSOR_X))
+    w = ji.weights(N, K, ji.seed_for(0, 0, ji.TENSOR_W))
+    qa = orc.quant_act(x)
+    qw, sw = orc.quant_weight(w)
+    ref = orc.gemm(qa["q_row"], qa["s_row"], qw, sw)
+    gx = jet.quant_act(dev_bf16(x))
+    gq, gs = jet.quant_weight(dev_bf16(w))
+    assert np.array_equal(host(gx["q_row"]), qa["q_row"]) and np.array_equal(host(gq), qw)
+    assert np.array_equal(host(gx["s_row"]), qa["s_row"]) and np.array_equal(host(gs), sw)
+    y = jet.fp8_linear_fwd(gx["q_row"], gx["s_row"], gq, gs)
+    check_gemm(host_bits(y), ref, "config0 fwd")
+
+
+@pytest.mark.parametrize("M", [1, 2, 8, 15, 16, 17, 32, 100, 128, 129, 300])
+def test_forward_ragged_M(jet, M):
+    y, ref = _fwd_case(jet, M, 256, 384, seed=100 + M)
+    check_gemm(y, ref, f"fwd M={M}")
+
+
+@pytest.mark.parametrize("N,K", [(128, 128), (1024, 4096), (384, 14336)])
+@pytest.mark.parametrize("M", [4, 160])
+def test_forward_shapes(jet, M, N, K):
+    y, ref = _fwd_case(jet, M, N, K, seed=7 * M + N)
+    check_gemm(y, ref, f"fwd {M}x{N}x{K}")
+
+
+@pytest.mark.parametrize("M,N,K", [(256, 384, 512), (5, 256, 128), (130, 128, 640)])
+def test_dgrad(jet, M, N, K):
+    dy, w = ji.grads(M, N, seed=M + 1), ji.weights(N, K, seed=M + 2)
+    qd = orc.quant_act(dy)
+    _, _, qwT, swT = orc.quant_weight(w, transposed=True)
+    ref = orc.gemm(qd["q_row"], qd["s_row"], qwT, swT)
+    assert ref["acc"].shape == (M, K)
+    dx = jet.fp8_linear_dgrad(dev(qd["q_row"]), dev(qd["s_row"]), dev(qwT), dev(swT))
+    assert tuple(dx.shape) == (M, K)
+    check_gemm(host_bits(dx), ref, f"dgrad {M}x{N}x{K}")
+
+
+@pytest.mark.parametrize("M,N,K", [(256, 384, 512), (128, 128, 128), (1024, 256, 128)])
+def test_wgrad(jet, M, N, K):
+    dy, x = ji.grads(M, N, seed=M + 3), ji.activations(M, K, seed=M + 4)
+    qd = orc.quant_act(dy, row=False, col=True)
+    qx = orc.quant_act(x, row=False, col=True)
+    ref = orc.gemm(qd["q_colT"], qd["s_colT"], qx["q_colT"], qx["s_colT"], sb_mode=orc.SB_ROW)
+    assert ref["acc"].shape == (N, K)
+    dw = jet.fp8_linear_wgrad(dev(qd["q_colT"]), dev(qd["s_colT"]), dev(qx["q_colT"]), dev(qx["s_colT"]))
+    assert tuple(dw.shape) == (N, K)
+    check_gemm(host_bits(dw), ref, f"wgrad {M}x{N}x{K}")
+
+
+def test_full_backward_from_fp8_saved_activation(jet):
+    """The backward pass as the method runs it: dY quantized both ways in one pass, the
+    FP8-saved X re-quantized along tokens, then DGrad and WGrad -- all on the GPU,
+    against the oracle doing the same steps."""
+    M, N, K = 384, 256, 512
+    x, w, dy = ji.activations(M, K, 11), ji.weights(N, K, 12), ji.grads(M, N, 13)
+    ox = orc.quant_act(x)
+    oxT = orc.quant_act(ox["q_row"], ox["s_row"], src=orc.SRC_FP8_ROW, row=False, col=True)
+    ody = orc.quant_act(dy, row=True, col=True)
+    _, _, oqT, osT = orc.quant_weight(w, transposed=True)
+    ref_dx = orc.gemm(ody["q_row"], ody["s_row"], oqT, osT)
+    ref_dw = orc.gemm(ody["q_colT"], ody["s_colT"], oxT["q_colT"], oxT["s_colT"], sb_mode=orc.SB_ROW)
+
+    gx = jet.quant_act(dev_bf16(x))
+    gxT = jet.quant_act(gx["q_row"], gx["s_row"], row=False, col=True)
+    gdy = jet.quant_act(dev_bf16(dy), row=True, col=True)
+    _, _, gqT, gsT = jet.quant_weight(dev_bf16(w), transposed=True)
+    dx = jet.fp8_linear_dgrad(gdy["q_row"], gdy["s_row"], gqT, gsT)
+    dw = jet.fp8_linear_wgrad(gdy["q_colT"], gdy["s_colT"], gxT["q_colT"], gxT["s_colT"])
+    assert np.array_equal(host(gxT["q_colT"]), oxT["q_colT"])
+    check_gemm(host_bits(dx), ref_dx, "backward dgrad")
+    check_gemm(host_bits(dw), ref_dw, "backward wgrad")
+
+
+def test_row_invariance_decode_vs_training_shapes(jet):
+    """A token row gives the same output bytes in every call that contains it: alone,
+    in small decode batches, and at seeded positions inside training-shaped calls."""
+    N, K = 512, 1024
+    R = ji.activations(128, K, seed=ji.seed_for(3, 0, ji.TENSOR_X))
+    w = ji.weights(N, K, seed=ji.seed_for(3, 0, ji.TENSOR_W))
+    gq, gs = jet.quant_weight(dev_bf16(w))
+    qR = jet.quant_act(dev_bf16(R))
+
+    def fwd(qx, sx):
+        return host_bits(jet.fp8_linear_fwd(qx.contiguous(), sx.contiguous(), gq, gs))
+
+    base = fwd(qR["q_row"], qR["s_row"])                     # M = 128
+    for M in (1, 8, 32):
+        perm = np.random.default_rng(M).permutation(128)[:M]
+        idx = torch.from_numpy(perm).to(qR["q_row"].device)
+        got = fwd(qR["q_row"][idx], qR["s_row"][idx])
+        assert np.array_equal(got, base[perm]), f"decode M={M} differs from M=128"
+    for M in (1000, 4096):
+        other = ji.activations(M, K, seed=900 + M)
+        pos = ji.row_positions(128, M, seed=ji.seed_for(3, 0, ji.TENSOR_POS) + M)
+        other[pos] = R
+        qo = jet.quant_act(dev_bf16(other))
+        got = fwd(qo["q_row"], qo["s_row"])
+        assert np.array_equal(got[pos], base), f"training M={M} differs from decode"
+
+
+def test_same_call_twice_same_bytes(jet):
+    M, N, K = 300, 256, 512
+    x, w = ji.activations(M, K, 1), ji.weights(N, K, 2)
+    gx = jet.quant_act(dev_bf16(x))
+    gq, gs = jet.quant_weight(dev_bf16(w))
+    a = jet.fp8_linear_fwd(gx["q_row"], gx["s_row"], gq, gs)
+    b = jet.fp8_linear_fwd(gx["q_row"], gx["s_row"], gq, gs)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_lossless_integer_case_is_exact(jet):
+    """Small integers times powers of two: every partial sum is exact in any order and
+    any accumulator width, so the GPU must reproduce the oracle bit for bit."""
+    rng = np.random.default_rng(1)
+    M, N, K = 40, 128, 256
+    xi = rng.integers(-4, 5, size=(M, K)).astype(np.float32)
+    wi = rng.integers(-4, 5, size=(N, K)).astype(np.float32)
+    xi[:, ::128] = 7.0
+    wi[0, ::128] = 7.0
+    qa = orc.quant_act(ji.f32_to_bf16_bits(xi * 64))         # amax 448 -> S = 1
+    qw, sw = orc.quant_weight(ji.f32_to_bf16_bits(wi * 64))
+    assert np.all(qa["s_row"] == 1.0) and np.all(sw == 1.0)
+    ref = orc.gemm(qa["q_row"], qa["s_row"], qw, sw)
+    assert np.array_equal(ref["acc"].astype(np.float64), ref["exact"])
+    y = jet.fp8_linear_fwd(dev(qa["q_row"]), dev(qa["s_row"]), dev(qw), dev(sw))
+    assert np.array_equal(host_bits(y), ref["out"])

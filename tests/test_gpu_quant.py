@@ -1,0 +1,138 @@
+"""GPU parity of the quantizers: FP8 codes and scales must be bit-identical to the
+oracle (Sec. 2.1 formula, Sec. 4.2 granularities)."""
+import numpy as np
+import pytest
+import torch
+
+import jet_inputs as ji
+import oracle as orc
+from jet_testlib import dev, dev_bf16, host
+
+pytestmark = pytest.mark.gpu
+G = 128
+
+
+@pytest.fixture(scope="module")
+def jet():
+    import paper_2601_14243_amd as j
+    assert torch.cuda.is_available()
+    j.lib()
+    return j
+
+
+def _cmp(name, got, want):
+    got = np.asarray(got)
+    if got.dtype == np.float32:
+        got, want = got.view(np.uint32), np.asarray(want, np.float32).view(np.uint32)
+    bad = np.argwhere(got != want)
+    assert bad.size == 0, f"{name}: {len(bad)} mismatches, first at {bad[0]}: got {got[tuple(bad[0])]} want {want[tuple(bad[0])]}"
+
+
+@pytest.mark.parametrize("M,K", [(256, 1024), (1, 128), (1, 4096), (3, 256), (17, 384), (200, 512), (129, 14336)])
+def test_row_quant_bf16(jet, M, K):
+    x = ji.activations(M, K, seed=ji.seed_for(0, 0, ji.TENSOR_X) + M)
+    want = orc.quant_act(x)
+    got = jet.quant_act(dev_bf16(x))
+    _cmp("q_row", host(got["q_row"]), want["q_row"])
+    _cmp("s_row", host(got["s_row"]), want["s_row"])
+
+
+@pytest.mark.parametrize("M,K", [(256, 1024), (128, 128), (384, 256), (1024, 640)])
+@pytest.mark.parametrize("mode", ["col", "dual"])
+def test_col_and_dual_quant_bf16(jet, M, K, mode):
+    x = ji.grads(M, K, seed=ji.seed_for(2, 0, ji.TENSOR_DY) + M + K)
+    row = mode == "dual"
+    want = orc.quant_act(x, row=row, col=True)
+    got = jet.quant_act(dev_bf16(x), row=row, col=True)
+    for k in want:
+        _cmp(k, host(got[k]), want[k])
+
+
+@pytest.mark.parametrize("M,K", [(256, 512), (384, 128)])
+@pytest.mark.parametrize("mode", ["row", "col", "dual"])
+def test_quant_from_fp8_saved_activation(jet, M, K, mode):
+    x = ji.activations(M, K, seed=77 + M)
+    first = orc.quant_act(x)
+    row, col = mode in ("row", "dual"), mode in ("col", "dual")
+    want = orc.quant_act(first["q_row"], first["s_row"], src=orc.SRC_FP8_ROW, row=row, col=col)
+    got = jet.quant_act(dev(first["q_row"]), dev(first["s_row"]), row=row, col=col)
+    for k in want:
+        _cmp(k, host(got[k]), want[k])
+
+
+def test_every_bf16_amax_and_special_values(jet):
+    """All 32639 positive finite bf16 values as a group's amax (from 2^-133 up to
+    3.39e38: subnormal scales, the IEEE fallback of the divider), signed zeros,
+    all-zero groups."""
+    h = np.arange(1, 0x7F80, dtype=np.uint16)
+    rng = np.random.default_rng(5)
+    a = orc.bf16_to_f32(h)
+    x = rng.uniform(-1, 1, size=(h.size, G)).astype(np.float32) * a[:, None]
+    xb = ji.f32_to_bf16_bits(x)
+    xb[:, 9] = h
+    xb[:, 10] = 0x8000          # -0.0
+    xb[:, 11] = 0x0000
+    xb[:, 12] = h | 0x8000
+    extra = np.zeros((3, G), np.uint16)
+    extra[1, :] = 0x8000        # a group of negative zeros
+    extra[2, 5] = 0x0001        # smallest subnormal alone
+    xb = np.concatenate([xb, extra])
+    pad = (-xb.shape[0]) % 128
+    xb = np.concatenate([xb, np.zeros((pad, G), np.uint16)])
+    want = orc.quant_act(xb, row=True, col=True)
+    got = jet.quant_act(dev_bf16(xb), row=True, col=True)
+    for k in want:
+        _cmp(k, host(got[k]), want[k])
+    got_row = jet.quant_act(dev_bf16(xb))
+    _cmp("row-only q", host(got_row["q_row"]), want["q_row"])
+    _cmp("row-only s", host(got_row["s_row"]), want["s_row"])
+
+
+def test_rounding_boundaries_through_the_quantizer(jet):
+    """Groups with amax = 448 * 2^j have S = 2^j exactly, so x / S is exact and the
+    codes probe the E4M3 rounding directly: every bf16 value of a binade range hits
+    ties, near-ties and the subnormal range."""
+    vals = np.arange(0x3000, 0x4400, dtype=np.uint16)       # bf16 from 2^-31.. up to 512
+    vals = vals[orc.bf16_to_f32(vals) <= 448.0]
+    vals = np.concatenate([vals, vals | 0x8000])
+    n = (vals.size + 126) // 127
+    xb = np.zeros((n, G), np.uint16)
+    flat = np.zeros(n * 127, np.uint16)
+    flat[: vals.size] = vals
+    xb[:, 1:] = flat.reshape(n, 127)
+    xb[:, 0] = 0x43E0                                        # 448.0
+    pad = (-n) % 128
+    xb = np.concatenate([xb, np.zeros((pad, G), np.uint16)])
+    want = orc.quant_act(xb, row=True, col=True)
+    assert np.all(want["s_row"][:n, 0] == 1.0)
+    got = jet.quant_act(dev_bf16(xb), row=True, col=True)
+    for k in want:
+        _cmp(k, host(got[k]), want[k])
+
+
+@pytest.mark.parametrize("N,K", [(1024, 1024), (128, 128), (384, 256), (256, 1152)])
+@pytest.mark.parametrize("transposed", [False, True])
+def test_weight_quant(jet, N, K, transposed):
+    w = ji.weights(N, K, seed=ji.seed_for(0, 0, ji.TENSOR_W) + N)
+    want = orc.quant_weight(w, transposed=transposed)
+    got = jet.quant_weight(dev_bf16(w), transposed=transposed)
+    for name, g, wv in zip(("q", "s", "qT", "sT"), got, want):
+        _cmp(name, host(g), wv)
+
+
+def test_weight_requant_after_update(jet):
+    w = ji.weights(256, 384, seed=3)
+    w2 = ji.weight_update(w, seed=4)
+    assert not np.array_equal(w, w2)
+    want = orc.quant_weight(w2, transposed=True)
+    got = jet.quant_weight(dev_bf16(w2), transposed=True)
+    for name, g, wv in zip(("q", "s", "qT", "sT"), got, want):
+        _cmp(name, host(g), wv)
+
+
+def test_same_call_twice_same_bytes(jet):
+    x = dev_bf16(ji.activations(256, 512, seed=1))
+    a = jet.quant_act(x, row=True, col=True)
+    b = jet.quant_act(x, row=True, col=True)
+    for k in a:
+        assert torch.equal(a[k], b[k])
