@@ -16,14 +16,22 @@
 namespace jet {
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
-typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
 
-// Lane-linear direct global->LDS copies: lane l's 16 (4) bytes land at lds + 16 l (4 l).
-__device__ __forceinline__ void load_to_lds16(const void* g, void* lds) {
-    __builtin_amdgcn_global_load_lds((gbl_ptr_t)g, (lds_ptr_t)lds, 16, 0, 0);
+// Lane-linear direct global->LDS copies (no VGPR staging): lane l's 16 (4) bytes land at
+// LDS address `lds` + 16 l (4 l).  `lds` and `base` must be wave-uniform.  Written as asm
+// so that the copy stays asynchronous: completion is awaited explicitly with
+// JET_WAIT_VMCNT + a workgroup barrier before any wave reads the data.
+__device__ __forceinline__ void dma16(uint32_t lds, const void* base, uint32_t voff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds), "v"(voff), "s"(base)
+                 : "memory");
 }
-__device__ __forceinline__ void load_to_lds4(const void* g, void* lds) {
-    __builtin_amdgcn_global_load_lds((gbl_ptr_t)g, (lds_ptr_t)lds, 4, 0, 0);
+__device__ __forceinline__ void dma4(uint32_t lds, const float* ptr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
+                 :
+                 : "s"(lds), "v"(ptr)
+                 : "memory");
 }
 
 // Hardware deals workgroup b to XCD b % 8; give every XCD a contiguous range of
@@ -34,29 +42,39 @@ __device__ __forceinline__ int xcd_contiguous_id(int b, int n) {
 }
 
 // ------------------------------------------------------------------------
-// Tile kernel: 128x128 output tile per workgroup, 4 waves as 2x2, each wave a
-// 64x64 sub-tile = 4x4 MFMA tiles.  Operand tiles of one group (128 rows x 128
-// bytes each) are copied global->LDS directly in MFMA fragment order (no VGPR
-// staging, conflict-free ds_read_b128), three stages deep.
+// Tile kernel.  A workgroup of WI x WJ waves owns a BM x BN output tile
+// (BM = WI*TM*16, BN = WJ*TN*16); a wave owns TM x TN MFMA tiles.  The operand
+// tiles of one group (BM + BN rows x 128 bytes) go global->LDS directly in MFMA
+// fragment order, so every ds_read_b128 is lane-linear and conflict-free; two
+// stages, the copy of group g+1 runs under the MFMAs of group g.
 //
-// LDS stage layout: [A tile 16 KB][B tile 16 KB][scales 1 KB]
+// LDS stage layout: [A tile BM*128][B tile BN*128][scales (BM+BN)*4]
 //   tile: fragment f (rows 16f..16f+15) at f*2048; half h at +h*1024; lane l at +l*16
 //         = row (l&15), bytes [64h + 16(l>>4), +16) of the group
-//   scales: wave w's 256 B = [sa rows 32w..32w+31][sb rows 32w..32w+31 | block scale]
+//   scales: wave w's 256 B = [sa rows 32w..32w+31][sb of columns 32w..32w+31]
+// Both configurations have BM = BN = 32 * waves, so every wave copies 4 A halves,
+// 4 B halves and one scale line per stage.
 // ------------------------------------------------------------------------
-constexpr int kStages = 3;
-constexpr int kTileBytes = 128 * 128;
-constexpr int kStageBytes = 2 * kTileBytes + 1024;
-constexpr int kLoadsPerStage = 9;  // per wave: 4 A halves, 4 B halves, 1 scale line
+template <int WI, int WJ, int TM, int TN>
+struct TileCfg {
+    static constexpr int kWaves = WI * WJ;
+    static constexpr int kThreads = 64 * kWaves;
+    static constexpr int BM = WI * TM * 16, BN = WJ * TN * 16;
+    static constexpr int kABytes = BM * 128, kBBytes = BN * 128;
+    static constexpr int kStageBytes = kABytes + kBBytes + (BM + BN) * 4;
+    static constexpr int kStages = 2;
+    static constexpr int kLdsBytes = kStages * kStageBytes;
+    static_assert(BM == 32 * kWaves && BN == 32 * kWaves, "copy schedule assumes BM = BN = 32 * waves");
+};
 
-template <int SB_MODE>
-__global__ __launch_bounds__(256) void gemm_tile_kernel(const uint8_t* __restrict__ A,
-                                                        const float* __restrict__ sa,
-                                                        const uint8_t* __restrict__ B,
-                                                        const float* __restrict__ sb,
-                                                        uint16_t* __restrict__ out, int I, int J, int R,
-                                                        int tiles_i, int tiles_j) {
+template <int SB_MODE, int WI, int WJ, int TM, int TN>
+__global__ __launch_bounds__(64 * WI * WJ, 512 / (64 * WI * WJ))
+void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ sa,
+                      const uint8_t* __restrict__ B, const float* __restrict__ sb,
+                      uint16_t* __restrict__ out, int I, int J, int R, int tiles_i, int tiles_j) {
+    using C = TileCfg<WI, WJ, TM, TN>;
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_ptr_t)smem;
     const int t = threadIdx.x, w = t >> 6, l = t & 63, r = l & 15, c4 = l >> 4;
     const int G = R / kGroup;
 
@@ -68,116 +86,107 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(const uint8_t* __restric
     const int rows_in_band = min(kBand, tiles_i - band * kBand);
     const int ti = band * kBand + within % rows_in_band;
     const int tj = within / rows_in_band;
-    const int i0 = ti * 128, j0 = tj * 128;
+    const int i0 = ti * C::BM, j0 = tj * C::BN;
 
-    // this wave copies A halves 4w..4w+3 and B halves 4w..4w+3 of every stage
-    const uint8_t* ga[4];
-    const uint8_t* gb[4];
+    // copy schedule of this wave: A halves 4w..4w+3, B halves 4w..4w+3, one scale line
+    const uint8_t* baseA = A + (size_t)i0 * R;
+    const uint8_t* baseB = B + (size_t)j0 * R;
+    uint32_t offA[4], offB[4];
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
         const int half = 4 * w + x, f = half >> 1, h = half & 1;
-        const int row_a = min(i0 + 16 * f + r, I - 1);
-        ga[x] = A + (size_t)row_a * R + 64 * h + 16 * c4;
-        gb[x] = B + (size_t)(j0 + 16 * f + r) * R + 64 * h + 16 * c4;
+        const int row_a = min(i0 + 16 * f + r, I - 1) - i0;   // rows past the end repeat the last one
+        offA[x] = (uint32_t)row_a * (uint32_t)R + 64 * h + 16 * c4;
+        offB[x] = (uint32_t)(16 * f + r) * (uint32_t)R + 64 * h + 16 * c4;
     }
     const float* gs;
     if (l < 32) {
         gs = sa + (size_t)min(i0 + 32 * w + l, I - 1) * G;
     } else if (SB_MODE == kSbBlock) {
-        gs = sb + (size_t)tj * G;
+        gs = sb + (size_t)((j0 + 32 * w + (l - 32)) >> 7) * G;
     } else {
         gs = sb + (size_t)(j0 + 32 * w + (l - 32)) * G;
     }
+    const uint32_t ldsw = __builtin_amdgcn_readfirstlane(lds0 + 4 * w * 1024);
+    const uint32_t ldss = __builtin_amdgcn_readfirstlane(lds0 + C::kABytes + C::kBBytes + w * 256);
 
     auto issue = [&](int g, int slot) {
-        uint8_t* st = smem + slot * kStageBytes;
+        const uint32_t st = slot * C::kStageBytes;
+        const uint8_t* ga = baseA + (size_t)g * kGroup;
+        const uint8_t* gb = baseB + (size_t)g * kGroup;
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
-            load_to_lds16(ga[x] + (size_t)g * kGroup, st + (4 * w + x) * 1024);
-            load_to_lds16(gb[x] + (size_t)g * kGroup, st + kTileBytes + (4 * w + x) * 1024);
+            dma16(ldsw + st + x * 1024, ga, offA[x]);
+            dma16(ldsw + st + C::kABytes + x * 1024, gb, offB[x]);
         }
-        load_to_lds4(gs + g, st + 2 * kTileBytes + w * 256);
+        dma4(ldss + st, gs + g);
     };
 
-    const int wi = w >> 1, wj = w & 1;
-    v4f acc[4][4];
+    const int wi = w / WJ, wj = w % WJ;
+    v4f acc[TM][TN];
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < TM; ++a)
 #pragma unroll
-        for (int b = 0; b < 4; ++b) acc[a][b] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+        for (int b = 0; b < TN; ++b) acc[a][b] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
 
-#pragma unroll
-    for (int s = 0; s < kStages - 1; ++s)
-        if (s < G) issue(s, s);
-
+    issue(0, 0);
     for (int g = 0; g < G; ++g) {
-        // group g landed when at most the younger stages' loads are outstanding
-        if (g + 1 < G) {
-            JET_WAIT_VMCNT(kLoadsPerStage * (kStages - 2));
-        } else {
-            JET_WAIT_VMCNT(0);
-        }
-        __syncthreads();
-        if (g + kStages - 1 < G) issue(g + kStages - 1, (g + kStages - 1) % kStages);
+        JET_WAIT_VMCNT(0);               // this wave's share of group g has landed
+        __builtin_amdgcn_s_barrier();    // ... and everybody else's; slot (g+1)&1 is free
+        asm volatile("" ::: "memory");
+        if (g + 1 < G) issue(g + 1, (g + 1) & 1);
 
-        const uint8_t* st = smem + (g % kStages) * kStageBytes;
-        const uint8_t* sc = st + 2 * kTileBytes;
-        v8i xf[4], cf[4];
+        const uint8_t* st = smem + (g & 1) * C::kStageBytes;
+        const uint8_t* sc = st + C::kABytes + C::kBBytes;
+        v8i cf[TN];
 #pragma unroll
-        for (int m = 0; m < 4; ++m) {
-            const uint8_t* p = st + (4 * wi + m) * 2048 + l * 16;
-            xf[m] = make_frag(*reinterpret_cast<const uint4*>(p), *reinterpret_cast<const uint4*>(p + 1024));
-        }
-#pragma unroll
-        for (int n = 0; n < 4; ++n) {
-            const uint8_t* p = st + kTileBytes + (4 * wj + n) * 2048 + l * 16;
+        for (int n = 0; n < TN; ++n) {
+            const uint8_t* p = st + C::kABytes + (wj * TN + n) * 2048 + l * 16;
             cf[n] = make_frag(*reinterpret_cast<const uint4*>(p), *reinterpret_cast<const uint4*>(p + 1024));
         }
-        float sai[4];
+        float sai[TM];
 #pragma unroll
-        for (int m = 0; m < 4; ++m) {
-            const int ii = 64 * wi + 16 * m + r;
+        for (int m = 0; m < TM; ++m) {
+            const int ii = (wi * TM + m) * 16 + r;
             sai[m] = *reinterpret_cast<const float*>(sc + (ii >> 5) * 256 + (ii & 31) * 4);
         }
+        v4f sbj[TN];
         if (SB_MODE == kSbBlock) {
-            const float sbv = *reinterpret_cast<const float*>(sc + 128);
-            float s[4];
+            const int jj = wj * TN * 16;   // the wave's columns share one 128-wide block
+            const float sbv = *reinterpret_cast<const float*>(sc + (jj >> 5) * 256 + 128 + (jj & 31) * 4);
 #pragma unroll
-            for (int m = 0; m < 4; ++m) s[m] = sai[m] * sbv;
-#pragma unroll
-            for (int m = 0; m < 4; ++m)
-#pragma unroll
-                for (int n = 0; n < 4; ++n) {
-                    const v4f p = group_product(cf[n], xf[m]);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[m][n][e] = chain(p[e], s[m], acc[m][n][e]);
-                }
+            for (int m = 0; m < TM; ++m) sai[m] *= sbv;
         } else {
-            v4f sbj[4];
 #pragma unroll
-            for (int n = 0; n < 4; ++n) {
-                const int jj = 64 * wj + 16 * n + 4 * c4;
+            for (int n = 0; n < TN; ++n) {
+                const int jj = (wj * TN + n) * 16 + 4 * c4;
                 sbj[n] = *reinterpret_cast<const v4f*>(sc + (jj >> 5) * 256 + 128 + (jj & 31) * 4);
             }
+        }
 #pragma unroll
-            for (int m = 0; m < 4; ++m)
+        for (int m = 0; m < TM; ++m) {
+            const uint8_t* p = st + (wi * TM + m) * 2048 + l * 16;
+            const v8i xf = make_frag(*reinterpret_cast<const uint4*>(p), *reinterpret_cast<const uint4*>(p + 1024));
 #pragma unroll
-                for (int n = 0; n < 4; ++n) {
-                    const v4f p = group_product(cf[n], xf[m]);
+            for (int n = 0; n < TN; ++n) {
+                const v4f pr = group_product(cf[n], xf);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[m][n][e] = chain(p[e], sai[m] * sbj[n][e], acc[m][n][e]);
+                for (int e = 0; e < 4; ++e) {
+                    const float s = (SB_MODE == kSbBlock) ? sai[m] : sai[m] * sbj[n][e];
+                    acc[m][n][e] = chain(pr[e], s, acc[m][n][e]);
                 }
+            }
         }
     }
 
-    // epilogue: lane holds 4 consecutive columns of one row per MFMA tile
+    // epilogue: a lane holds 4 consecutive columns of one row per MFMA tile
 #pragma unroll
-    for (int m = 0; m < 4; ++m) {
-        const int i = i0 + 64 * wi + 16 * m + r;
+    for (int m = 0; m < TM; ++m) {
+        const int i = i0 + (wi * TM + m) * 16 + r;
         if (i < I) {
 #pragma unroll
-            for (int n = 0; n < 4; ++n) {
-                const int j = j0 + 64 * wj + 16 * n + 4 * c4;
+            for (int n = 0; n < TN; ++n) {
+                const int j = j0 + (wj * TN + n) * 16 + 4 * c4;
                 uint2 o;
                 o.x = bf16_rne(acc[m][n][0]) | (bf16_rne(acc[m][n][1]) << 16);
                 o.y = bf16_rne(acc[m][n][2]) | (bf16_rne(acc[m][n][3]) << 16);
@@ -272,13 +281,40 @@ static hipError_t allow_lds(K kernel, int bytes) {
                                hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
+// big tile: 256x256, 8 waves of 128x64;  small tile: 128x128, 4 waves of 64x64
+#define JET_BIG 2, 4, 8, 4
+#define JET_SMALL 2, 2, 4, 4
+using BigCfg = TileCfg<JET_BIG>;
+using SmallCfg = TileCfg<JET_SMALL>;
+
+template <int SB_MODE>
+static hipError_t launch_tile(const uint8_t* A, const float* sa, const uint8_t* B, const float* sb,
+                              uint16_t* o, long I, long J, long R, hipStream_t st) {
+    // shape-only choice: the big tile when it divides J and fills the 256 CUs
+    const long big_tiles = ((I + 255) / 256) * (J / 256);
+    if (J % 256 == 0 && big_tiles >= 224) {
+        const int ti = (int)((I + 255) / 256), tj = (int)(J / 256);
+        hipLaunchKernelGGL((gemm_tile_kernel<SB_MODE, JET_BIG>), dim3((unsigned)(ti * tj)),
+                           dim3(BigCfg::kThreads), BigCfg::kLdsBytes, st, A, sa, B, sb, o, (int)I, (int)J,
+                           (int)R, ti, tj);
+    } else {
+        const int ti = (int)((I + 127) / 128), tj = (int)(J / 128);
+        hipLaunchKernelGGL((gemm_tile_kernel<SB_MODE, JET_SMALL>), dim3((unsigned)(ti * tj)),
+                           dim3(SmallCfg::kThreads), SmallCfg::kLdsBytes, st, A, sa, B, sb, o, (int)I,
+                           (int)J, (int)R, ti, tj);
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_gemm(const uint8_t* A, const float* sa, const uint8_t* B, const float* sb,
                        int sb_mode, void* out, long I, long J, long R, hipStream_t st) {
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [] {
-        hipError_t e = allow_lds(gemm_tile_kernel<kSbBlock>, kStages * kStageBytes);
-        if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbRow>, kStages * kStageBytes);
+        hipError_t e = allow_lds(gemm_tile_kernel<kSbBlock, JET_BIG>, BigCfg::kLdsBytes);
+        if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbRow, JET_BIG>, BigCfg::kLdsBytes);
+        if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbBlock, JET_SMALL>, SmallCfg::kLdsBytes);
+        if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbRow, JET_SMALL>, SmallCfg::kLdsBytes);
         if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel, kSkinnyPass * kSkinnyGroupBytes);
         attr_err = e;
     });
@@ -290,16 +326,8 @@ hipError_t launch_gemm(const uint8_t* A, const float* sa, const uint8_t* B, cons
                            kSkinnyPass * kSkinnyGroupBytes, st, A, sa, B, sb, o, (int)I, (int)J, (int)R);
         return hipGetLastError();
     }
-    const int tiles_i = (int)((I + 127) / 128), tiles_j = (int)(J / 128);
-    dim3 grid((unsigned)(tiles_i * tiles_j));
-    if (sb_mode == kSbBlock) {
-        hipLaunchKernelGGL(gemm_tile_kernel<kSbBlock>, grid, dim3(256), kStages * kStageBytes, st, A, sa,
-                           B, sb, o, (int)I, (int)J, (int)R, tiles_i, tiles_j);
-    } else {
-        hipLaunchKernelGGL(gemm_tile_kernel<kSbRow>, grid, dim3(256), kStages * kStageBytes, st, A, sa, B,
-                           sb, o, (int)I, (int)J, (int)R, tiles_i, tiles_j);
-    }
-    return hipGetLastError();
+    if (sb_mode == kSbBlock) return launch_tile<kSbBlock>(A, sa, B, sb, o, I, J, R, st);
+    return launch_tile<kSbRow>(A, sa, B, sb, o, I, J, R, st);
 }
 
 }  // namespace jet
