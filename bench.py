@@ -1,0 +1,267 @@
+#!/usr/bin/env python3
+"""Benchmark of the block-scaled FP8 linear layer on one MI355X.
+
+One "step" is one pass of the whole hot path over the seven linears of an
+8B-class decoder layer (hidden 4096, q/k/v/o, gate/up 14336, down) on synthetic
+inputs already resident in HBM:
+  training, M = 16384 tokens, per matrix: weight quantization with transposed copy,
+  row quantization of X, FProp, fused row+column quantization of dY, DGrad,
+  column re-quantization of the FP8-saved X, WGrad;
+  rollout, M in {1, 8, 32, 128}: row quantization of the activations and FProp
+  against the weights quantized above.
+`value` is the GEMM work of the training part (3 GEMMs x 2 M N K per matrix)
+divided by the time of the whole step (quantizers and decode calls included).
+
+Prints ONE JSON line (see --help for the flags the driver passes).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_FP8_TFLOPS = 5000.0     # MI355X dense FP8 MFMA peak
+PEAK_HBM_GBPS = 8000.0
+M_TRAIN = 16384
+DECODE_M = (1, 8, 32, 128)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode-sweep", action="store_true")
+    return ap.parse_args()
+
+
+def make_inputs(torch, jet, M, layer):
+    """Seeded synthetic tensors with the structure of jet_inputs' recipes, drawn on the
+    GPU (same distributions; the parity tests use the host generator)."""
+    dev = "cuda:0"
+    gen = torch.Generator(device=dev)
+    mats = []
+    for idx, (name, N, K) in enumerate(layer):
+        gen.manual_seed(2000 + 10 * idx)
+        x = torch.randn((M, K), generator=gen, device=dev, dtype=torch.float32)
+        n_out = -(-K // 100)
+        cols = torch.randperm(K, generator=gen, device=dev)[:n_out]
+        x[:, cols] *= 50.0
+        x = x.to(torch.bfloat16)
+        w = (torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32) * 0.02).to(torch.bfloat16)
+        dy = torch.randn((M, N), generator=gen, device=dev, dtype=torch.float32) * 1e-3
+        mask = torch.rand((M, N), generator=gen, device=dev) < 0.005
+        # Student-t(3) = normal / sqrt(chi2_3 / 3)
+        z = torch.randn((M, N), generator=gen, device=dev)
+        chi = (torch.randn((3, M, N), generator=gen, device=dev) ** 2).sum(0) / 3.0
+        dy = torch.where(mask, 1e-3 * z / chi.sqrt(), dy).to(torch.bfloat16)
+        del z, chi, mask
+        u8, f32, bf = torch.uint8, torch.float32, torch.bfloat16
+        e = lambda shape, dt: torch.empty(shape, dtype=dt, device=dev)
+        m = dict(name=name, N=N, K=K, x=x, w=w, dy=dy,
+                 qx=dict(q_row=e((M, K), u8), s_row=e((M, K // 128), f32)),
+                 qxT=dict(q_colT=e((K, M), u8), s_colT=e((K, M // 128), f32)),
+                 qdy=dict(q_row=e((M, N), u8), s_row=e((M, N // 128), f32),
+                          q_colT=e((N, M), u8), s_colT=e((N, M // 128), f32)),
+                 qw=(e((N, K), u8), e((N // 128, K // 128), f32), e((K, N), u8), e((K // 128, N // 128), f32)),
+                 y=e((M, N), bf), dx=e((M, K), bf), dw=e((N, K), bf), dec=[])
+        for Md in DECODE_M:
+            xd = x[:Md].contiguous()
+            m["dec"].append(dict(M=Md, x=xd, q=dict(q_row=e((Md, K), u8), s_row=e((Md, K // 128), f32)),
+                                 y=e((Md, N), bf)))
+        mats.append(m)
+    return mats
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures ONE GPU; run with --gpus 1 "
+              "(no collective or multi-GPU path exists in this library)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import jet_inputs as ji
+    import paper_2601_14243_amd as jet
+
+    if not torch.cuda.is_available():
+        print("bench.py: needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    jet.lib()
+    torch.cuda.set_device(0)
+    layer = ji.LAYER_8B
+    M = M_TRAIN
+    mats = make_inputs(torch, jet, M, layer)
+    sum_nk = sum(N * K for _, N, K in layer)
+    flops_step = 3 * 2 * M * sum_nk
+
+    gemm_events = []   # (start, end, flops) around the block-scaled tile GEMM (FProp, DGrad)
+    wgrad_events = []
+    quant_events = []  # (start, end, bytes)
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def timed(store, work, fn):
+        if store is None:
+            fn()
+            return
+        a, b = ev(), ev()
+        a.record()
+        fn()
+        b.record()
+        store.append((a, b, work))
+
+    def step(record):
+        ge = gemm_events if record else None
+        we = wgrad_events if record else None
+        qe = quant_events if record else None
+        for m in mats:
+            N, K = m["N"], m["K"]
+            fl = 2 * M * N * K
+            timed(qe, N * K * 4.0, lambda: jet.quant_weight(m["w"], transposed=True, out=m["qw"]))
+            timed(qe, M * K * 3.03125, lambda: jet.quant_act(m["x"], out=m["qx"]))
+            timed(ge, fl, lambda: jet.fp8_linear_fwd(m["qx"]["q_row"], m["qx"]["s_row"], m["qw"][0], m["qw"][1], out=m["y"]))
+            timed(qe, M * N * 4.0625, lambda: jet.quant_act(m["dy"], row=True, col=True, out=m["qdy"]))
+            timed(ge, fl, lambda: jet.fp8_linear_dgrad(m["qdy"]["q_row"], m["qdy"]["s_row"], m["qw"][2], m["qw"][3], out=m["dx"]))
+            timed(qe, M * K * 2.0625, lambda: jet.quant_act(m["qx"]["q_row"], m["qx"]["s_row"], row=False, col=True, out=m["qxT"]))
+            timed(we, fl, lambda: jet.fp8_linear_wgrad(m["qdy"]["q_colT"], m["qdy"]["s_colT"], m["qxT"]["q_colT"], m["qxT"]["s_colT"], out=m["dw"]))
+            for d in m["dec"]:
+                jet.quant_act(d["x"], out=d["q"])
+                jet.fp8_linear_fwd(d["q"]["q_row"], d["q"]["s_row"], m["qw"][0], m["qw"][1], out=d["y"])
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = flops_step / (ms_per_step * 1e-3) / 1e12
+
+    def rate(events):
+        tot_t = sum(a.elapsed_time(b) for a, b, _ in events) * 1e-3
+        tot_w = sum(w for _, _, w in events)
+        return tot_w / tot_t, tot_t / len(events), tot_w / len(events)
+
+    g_rate, g_avg_s, g_avg_fl = rate(gemm_events)
+    w_rate, w_avg_s, _ = rate(wgrad_events)
+    q_rate, _, _ = rate(quant_events)
+    gemm_time = sum(a.elapsed_time(b) for a, b, _ in gemm_events + wgrad_events) * 1e-3 / args.steps
+    out = {
+        "metric": "FP8 linear TFLOP/s (train fwd+bwd, M=16k) + decode GEMM HBM GB/s (M=1..128)",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "fp8_e4m3 x fp8_e4m3 -> f32 -> bf16",
+        "data": "synthetic",
+        "config": {"workload": "8B-class decoder layer, 7 linears, training M=16384 (quantizers + "
+                               "FProp + DGrad + WGrad) plus rollout FProp at M in {1,8,32,128}",
+                   "sum_NK": sum_nk, "train_gemm_flop_per_step": flops_step},
+        "train_gemm_only_tflops": round(flops_step / gemm_time / 1e12, 2),
+        "fprop_dgrad_kernel_tflops": round(g_rate / 1e12, 2),
+        "wgrad_kernel_tflops": round(w_rate / 1e12, 2),
+        "quantizers_gbps": round(q_rate / 1e9, 1),
+        "roofline": {"bound": "mfma", "kernel": "gemm_tile_kernel (FProp/DGrad, 1x128 x 128x128 scales)",
+                     "achieved": round(g_rate / 1e12, 2), "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(g_rate / 1e12 / PEAK_FP8_TFLOPS, 4),
+                     "avg_launch_ms": round(g_avg_s * 1e3, 4), "avg_launch_gflop": round(g_avg_fl / 1e9, 2),
+                     "launches": len(gemm_events), "traffic": None},
+    }
+
+    if not args.no_decode_sweep:
+        out["decode"] = decode_sweep(torch, jet, layer)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(out))
+
+
+def decode_sweep(torch, jet, layer, rotations=4):
+    """Rollout FProp over the layer with `rotations` distinct weight sets (> 256 MB each
+    pass, so weights come from HBM, not from the last-level cache); one HIP graph per M
+    replayed several times; GB/s = algorithmic bytes / time."""
+    dev = "cuda:0"
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(4242)
+    sets = []
+    for _ in range(rotations):
+        ws = []
+        for _, N, K in layer:
+            w = (torch.randn((N, K), generator=gen, device=dev) * 0.02).to(torch.bfloat16)
+            ws.append(jet.quant_weight(w))
+            del w
+        sets.append(ws)
+    res = {}
+    for Md in DECODE_M + (16,):
+        acts, outs = [], []
+        for _, N, K in layer:
+            x = torch.randn((Md, K), generator=gen, device=dev).to(torch.bfloat16)
+            acts.append(jet.quant_act(x))
+            outs.append(torch.empty((Md, N), dtype=torch.bfloat16, device=dev))
+
+        def run():
+            for ws in sets:
+                for (q, s), a, y in zip(ws, acts, outs):
+                    jet.fp8_linear_fwd(a["q_row"], a["s_row"], q, s, out=y)
+
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            run()
+        torch.cuda.current_stream().wait_stream(s)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            run()
+        g.replay()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 10
+        a.record()
+        for _ in range(reps):
+            g.replay()
+        b.record()
+        torch.cuda.synchronize()
+        t_layer = a.elapsed_time(b) * 1e-3 / (reps * rotations)
+        by = sum(N * K + 4 * (N // 128) * (K // 128) + Md * K + 4 * Md * (K // 128) + 2 * Md * N for _, N, K in layer)
+        res[f"M={Md}"] = {"us_per_layer": round(t_layer * 1e6, 2), "GB/s": round(by / t_layer / 1e9, 1),
+                          "frac_hbm": round(by / t_layer / 1e9 / PEAK_HBM_GBPS, 4)}
+    return res
+
+
+def cpu_baseline():
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: the small
+    configuration's shapes (N = K = 1024) with M scaled to roughly 15 s of CPU work."""
+    import jet_inputs as ji
+    import oracle as orc
+
+    def run(M, N, K):
+        x, w, dy = ji.activations(M, K, 1), ji.weights(N, K, 2), ji.grads(M, N, 3)
+        t0 = time.perf_counter()
+        qx = orc.quant_act(x)
+        qw, sw, qwT, swT = orc.quant_weight(w, transposed=True)
+        qdy = orc.quant_act(dy, row=True, col=True)
+        qxT = orc.quant_act(qx["q_row"], qx["s_row"], src=orc.SRC_FP8_ROW, row=False, col=True)
+        orc.fp8_linear_fwd(qx["q_row"], qx["s_row"], qw, sw)
+        orc.fp8_linear_dgrad(qdy["q_row"], qdy["s_row"], qwT, swT)
+        orc.fp8_linear_wgrad(qdy["q_colT"], qdy["s_colT"], qxT["q_colT"], qxT["s_colT"])
+        return time.perf_counter() - t0
+
+    N = K = 1024
+    t_small = run(128, N, K)
+    k = int(min(32, max(1, round(15.0 / max(t_small, 1e-3)))))
+    M = 128 * k
+    t = run(M, N, K)
+    fl = 3 * 2 * M * N * K
+    return {"value": round(fl / t / 1e12, 6), "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"one linear N=K=1024, M={M}: quantizers + FProp + DGrad + WGrad, {t:.1f} s"}
+
+
+if __name__ == "__main__":
+    main()
