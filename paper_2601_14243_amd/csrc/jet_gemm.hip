@@ -45,12 +45,14 @@ __device__ __forceinline__ int xcd_contiguous_id(int b, int n) {
 // Tile kernel.  A workgroup of WI x WJ waves owns a BM x BN output tile
 // (BM = WI*TM*16, BN = WJ*TN*16); a wave owns TM x TN MFMA tiles.  The operand
 // tiles of one group (BM + BN rows x 128 bytes) go global->LDS directly in MFMA
-// fragment order, so every ds_read_b128 is lane-linear and conflict-free; two
-// stages, the copy of group g+1 runs under the MFMAs of group g.
+// whole cache lines, swizzled so that every fragment ds_read_b128 is conflict-free;
+// two stages, the copy of group g+1 runs under the MFMAs of group g.
 //
 // LDS stage layout: [A tile BM*128][B tile BN*128][scales (BM+BN)*4]
-//   tile: fragment f (rows 16f..16f+15) at f*2048; half h at +h*1024; lane l at +l*16
-//         = row (l&15), bytes [64h + 16(l>>4), +16) of the group
+//   tile: 1 KB block per 8 rows; row q (0..7) of a block keeps its eight 16-byte chunks at
+//         q*128 + 16*(c ^ swz), swz = ((row>>1)&7): one copy instruction moves 8 whole
+//         128-byte lines (8 consecutive lanes = one line), and the 16 lanes of an MFMA
+//         fragment read (rows 0..15, same chunk) hit 16 different 16-byte bank groups
 //   scales: wave w's 256 B = [sa rows 32w..32w+31][sb of columns 32w..32w+31]
 // Both configurations have BM = BN = 32 * waves, so every wave copies 4 A halves,
 // 4 B halves and one scale line per stage.
@@ -94,11 +96,16 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
     uint32_t offA[4], offB[4];
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
-        const int half = 4 * w + x, f = half >> 1, h = half & 1;
-        const int row_a = min(i0 + 16 * f + r, I - 1) - i0;   // rows past the end repeat the last one
-        offA[x] = (uint32_t)row_a * (uint32_t)R + 64 * h + 16 * c4;
-        offB[x] = (uint32_t)(16 * f + r) * (uint32_t)R + 64 * h + 16 * c4;
+        const int row = 32 * w + 8 * x + (l >> 3);             // row of the tile this lane copies
+        const int chunk = (l & 7) ^ ((row >> 1) & 7);
+        const int row_a = min(i0 + row, I - 1) - i0;           // rows past the end repeat the last one
+        offA[x] = (uint32_t)row_a * (uint32_t)R + 16 * chunk;
+        offB[x] = (uint32_t)row * (uint32_t)R + 16 * chunk;
     }
+    // where this lane's two 16-byte pieces of a fragment (row r, chunks c4 and 4 + c4) sit
+    const int swz = (r >> 1) & 7;
+    const int frag_lo = (r >> 3) * 1024 + (r & 7) * 128 + 16 * (c4 ^ swz);
+    const int frag_hi = (r >> 3) * 1024 + (r & 7) * 128 + 16 * ((4 + c4) ^ swz);
     const float* gs;
     if (l < 32) {
         gs = sa + (size_t)min(i0 + 32 * w + l, I - 1) * G;
@@ -141,8 +148,8 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
         v8i cf[TN];
 #pragma unroll
         for (int n = 0; n < TN; ++n) {
-            const uint8_t* p = st + C::kABytes + (wj * TN + n) * 2048 + l * 16;
-            cf[n] = make_frag(*reinterpret_cast<const uint4*>(p), *reinterpret_cast<const uint4*>(p + 1024));
+            const uint8_t* p = st + C::kABytes + (wj * TN + n) * 2048;
+            cf[n] = make_frag(*reinterpret_cast<const uint4*>(p + frag_lo), *reinterpret_cast<const uint4*>(p + frag_hi));
         }
         float sai[TM];
 #pragma unroll
@@ -165,8 +172,8 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
         }
 #pragma unroll
         for (int m = 0; m < TM; ++m) {
-            const uint8_t* p = st + (wi * TM + m) * 2048 + l * 16;
-            const v8i xf = make_frag(*reinterpret_cast<const uint4*>(p), *reinterpret_cast<const uint4*>(p + 1024));
+            const uint8_t* p = st + (wi * TM + m) * 2048;
+            const v8i xf = make_frag(*reinterpret_cast<const uint4*>(p + frag_lo), *reinterpret_cast<const uint4*>(p + frag_hi));
 #pragma unroll
             for (int n = 0; n < TN; ++n) {
                 const v4f pr = group_product(cf[n], xf);
