@@ -21,13 +21,22 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 // LDS address `lds` + 16 l (4 l).  `lds` and `base` must be wave-uniform.  Written as asm
 // so that the copy stays asynchronous: completion is awaited explicitly with
 // JET_WAIT_VMCNT + a workgroup barrier before any wave reads the data.
+__device__ __forceinline__ const void* uniform_ptr(const void* p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const void*>(((uint64_t)hi << 32) | lo);
+}
 __device__ __forceinline__ void dma16(uint32_t lds, const void* base, uint32_t voff) {
+    lds = __builtin_amdgcn_readfirstlane(lds);
+    base = uniform_ptr(base);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
                  : "s"(lds), "v"(voff), "s"(base)
                  : "memory");
 }
 __device__ __forceinline__ void dma4(uint32_t lds, const float* ptr) {
+    lds = __builtin_amdgcn_readfirstlane(lds);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
                  :
                  : "s"(lds), "v"(ptr)
@@ -231,79 +240,111 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
 
 // ------------------------------------------------------------------------
 // Skinny kernel for I <= 16 (decode): bound by streaming B (the weights) once.
-// One workgroup of 8 waves owns 16 output columns and the whole reduction; the
-// waves split the groups, each streaming its weight fragments straight from
-// global memory into MFMA registers with a deep prefetch queue.  The p_g and
-// s_g of all groups meet in LDS, where waves 0-3 run the ordered fma chain.
+// A workgroup of 4 waves owns 16 output columns and the whole reduction.  The
+// groups are dealt to the waves in runs of 8; every wave streams its own units
+// (16 weight rows + the 16 activation rows + scales of one group, 4.25 KB) through
+// a private LDS ring with kSkDepth units in flight, using the same whole-line
+// LDS-DMA and swizzled fragment layout as the tile kernel -- no barrier is needed
+// for the ring.  Every 32 groups the p_g and s_g meet in LDS and the four waves run
+// the ordered fma chain for their quarter of the outputs.
 // ------------------------------------------------------------------------
-constexpr int kSkinnyWaves = 8;
-constexpr int kSkinnyPass = 112;                    // groups resident in LDS at once
-constexpr int kSkinnyGroupBytes = 4 * 64 * 4 + 64 * 4;  // p[4][64] + s[64]
-constexpr int kSkinnyDepth = 8;                     // weight fragments in flight per wave
+constexpr int kSkWaves = 4;
+constexpr int kSkRun = 8;                                // consecutive groups per wave per pass
+constexpr int kSkPass = kSkWaves * kSkRun;               // groups chained per pass
+constexpr int kSkDepth = 6;                              // units in flight per wave
+constexpr int kSkUnitBytes = 2048 + 2048 + 256;          // weight fragment, activation fragment, scales
+constexpr int kSkRingBytes = kSkDepth * kSkUnitBytes;
+constexpr int kSkGroupBytes = 4 * 64 * 4 + 64 * 4;       // p[4][64] + s[64]
+constexpr int kSkLdsBytes = kSkWaves * kSkRingBytes + kSkPass * kSkGroupBytes;
+constexpr int kSkCopies = 5;                             // vector-memory operations per unit
 
-__global__ __launch_bounds__(512) void gemm_skinny_kernel(const uint8_t* __restrict__ A,
-                                                          const float* __restrict__ sa,
-                                                          const uint8_t* __restrict__ B,
-                                                          const float* __restrict__ sb,
-                                                          uint16_t* __restrict__ out, int I, int J, int R) {
+__global__ __launch_bounds__(64 * kSkWaves) void gemm_skinny_kernel(const uint8_t* __restrict__ A,
+                                                                     const float* __restrict__ sa,
+                                                                     const uint8_t* __restrict__ B,
+                                                                     const float* __restrict__ sb,
+                                                                     uint16_t* __restrict__ out, int I, int J,
+                                                                     int R) {
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_ptr_t)smem;
     const int t = threadIdx.x, w = t >> 6, l = t & 63, r = l & 15, c4 = l >> 4;
     const int G = R / kGroup;
     const int j0 = blockIdx.x * 16;
-    const int ia = min(r, I - 1);
 
-    const uint8_t* gb = B + (size_t)(j0 + r) * R + 16 * c4;
-    const uint8_t* ga = A + (size_t)ia * R + 16 * c4;
-    const float* gsa = sa + (size_t)ia * G;
-    const float* gsb = sb + (size_t)(j0 >> 7) * G;
-
-    float acc = 0.0f;  // waves 0-3: output (row r, column j0 + 4 c4 + w)
-
-    for (int g0 = 0; g0 < G; g0 += kSkinnyPass) {
-        const int ng = min(kSkinnyPass, G - g0);
-        const int per = (ng + kSkinnyWaves - 1) / kSkinnyWaves;
-        const int gbeg = g0 + min(w * per, ng), gend = g0 + min((w + 1) * per, ng);
-
-        if (gbeg < gend) {
-            // queue of operand fragments and scales, kSkinnyDepth groups ahead; indices are
-            // clamped to the wave's last group, so the tail repeats it (same values, same slot)
-            const int last = gend - 1;
-            uint4 wlo[kSkinnyDepth], whi[kSkinnyDepth], xlo[kSkinnyDepth], xhi[kSkinnyDepth];
-            float qa[kSkinnyDepth], qb[kSkinnyDepth];
-            auto fetch = [&](int d, int g) {
-                wlo[d] = *reinterpret_cast<const uint4*>(gb + (size_t)g * kGroup);
-                whi[d] = *reinterpret_cast<const uint4*>(gb + (size_t)g * kGroup + 64);
-                xlo[d] = *reinterpret_cast<const uint4*>(ga + (size_t)g * kGroup);
-                xhi[d] = *reinterpret_cast<const uint4*>(ga + (size_t)g * kGroup + 64);
-                qa[d] = gsa[g];
-                qb[d] = gsb[g];
-            };
+    // copy offsets of this lane: block b = rows 8b..8b+7 of a fragment, one line per 8 lanes
+    uint32_t offW[2], offX[2];
 #pragma unroll
-            for (int d = 0; d < kSkinnyDepth; ++d) fetch(d, min(gbeg + d, last));
-            for (int gq = gbeg; gq < gend; gq += kSkinnyDepth) {
-#pragma unroll
-                for (int d = 0; d < kSkinnyDepth; ++d) {
-                    const int g = min(gq + d, last);
-                    const v4f p = group_product(make_frag(wlo[d], whi[d]), make_frag(xlo[d], xhi[d]));
-                    const float s = qa[d] * qb[d];
-                    fetch(d, min(gq + d + kSkinnyDepth, last));
-                    float* dst = reinterpret_cast<float*>(smem + (g - g0) * kSkinnyGroupBytes);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) dst[e * 64 + l] = p[e];
-                    dst[256 + l] = s;
-                }
+    for (int b = 0; b < 2; ++b) {
+        const int row = 8 * b + (l >> 3);
+        const int chunk = (l & 7) ^ ((row >> 1) & 7);
+        offW[b] = (uint32_t)row * (uint32_t)R + 16 * chunk;
+        offX[b] = (uint32_t)min(row, I - 1) * (uint32_t)R + 16 * chunk;
+    }
+    const uint8_t* baseW = B + (size_t)j0 * R;
+    // scale line of a unit: lanes 0-15 fetch sa of rows 0-15 (clamped), the rest the block scale
+    const float* gs = (l < 16) ? sa + (size_t)min(l, I - 1) * G : sb + (size_t)(j0 >> 7) * G;
+    const int swz = (r >> 1) & 7;
+    const int frag_lo = (r >> 3) * 1024 + (r & 7) * 128 + 16 * (c4 ^ swz);
+    const int frag_hi = (r >> 3) * 1024 + (r & 7) * 128 + 16 * ((4 + c4) ^ swz);
+
+    const uint32_t ring = __builtin_amdgcn_readfirstlane(lds0 + w * kSkRingBytes);
+    uint8_t* const ring_p = smem + w * kSkRingBytes;
+    uint8_t* const pass_p = smem + kSkWaves * kSkRingBytes;
+
+    // unit i of this wave is group seq(i); the wave has n_units of them
+    auto seq = [&](int i) { return (i / kSkRun) * kSkPass + w * kSkRun + (i % kSkRun); };
+    const int full = G / kSkPass, tail = G - full * kSkPass;
+    const int n_units = full * kSkRun + max(0, min(kSkRun, tail - w * kSkRun));
+
+    auto issue = [&](int i) {
+        const int g = seq(i);
+        const uint32_t u = ring + (i % kSkDepth) * kSkUnitBytes;
+        dma16(u, baseW + (size_t)g * kGroup, offW[0]);
+        dma16(u + 1024, baseW + (size_t)g * kGroup, offW[1]);
+        dma16(u + 2048, A + (size_t)g * kGroup, offX[0]);
+        dma16(u + 3072, A + (size_t)g * kGroup, offX[1]);
+        dma4(u + 4096, gs + g);
+    };
+
+    for (int i = 0; i < kSkDepth && i < n_units; ++i) issue(i);
+
+    float acc = 0.0f;  // output (row r, column j0 + 4 c4 + w)
+    int i = 0;
+    for (int g0 = 0; g0 < G; g0 += kSkPass) {
+        const int ng = min(kSkPass, G - g0);
+        for (int j = 0; j < kSkRun; ++j, ++i) {
+            if (i >= n_units) break;                 // wave-uniform
+            // unit i has landed once at most the younger units' copies are outstanding
+            const int younger = min(n_units, i + kSkDepth) - i - 1;
+            switch (younger) {
+                case 0: JET_WAIT_VMCNT(0); break;
+                case 1: JET_WAIT_VMCNT(kSkCopies); break;
+                case 2: JET_WAIT_VMCNT(2 * kSkCopies); break;
+                case 3: JET_WAIT_VMCNT(3 * kSkCopies); break;
+                case 4: JET_WAIT_VMCNT(4 * kSkCopies); break;
+                default: JET_WAIT_VMCNT(5 * kSkCopies); break;
             }
+            asm volatile("" ::: "memory");
+            const uint8_t* u = ring_p + (i % kSkDepth) * kSkUnitBytes;
+            const v8i wf = load_frag(u + frag_lo, u + frag_hi);
+            const v8i xf = load_frag(u + 2048 + frag_lo, u + 2048 + frag_hi);
+            const float s = *reinterpret_cast<const float*>(u + 4096 + 4 * r) *
+                            *reinterpret_cast<const float*>(u + 4096 + 64);
+            const v4f p = group_product(wf, xf);
+            float* dst = reinterpret_cast<float*>(pass_p + (seq(i) - g0) * kSkGroupBytes);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) dst[e * 64 + l] = p[e];
+            dst[256 + l] = s;
+            asm volatile("" ::: "memory");
+            if (i + kSkDepth < n_units) issue(i + kSkDepth);
         }
         __syncthreads();
-        if (w < 4) {
-            for (int g = 0; g < ng; ++g) {
-                const float* src = reinterpret_cast<const float*>(smem + g * kSkinnyGroupBytes);
-                acc = chain(src[w * 64 + l], src[256 + l], acc);
-            }
+        for (int g = 0; g < ng; ++g) {
+            const float* src = reinterpret_cast<const float*>(pass_p + g * kSkGroupBytes);
+            acc = chain(src[w * 64 + l], src[256 + l], acc);
         }
         __syncthreads();
     }
-    if (w < 4 && r < I) out[(size_t)r * J + j0 + 4 * c4 + w] = (uint16_t)bf16_rne(acc);
+    if (r < I) out[(size_t)r * J + j0 + 4 * c4 + w] = (uint16_t)bf16_rne(acc);
 }
 
 // ----------------------------------------------------------------- launch --
@@ -348,15 +389,15 @@ hipError_t launch_gemm(const uint8_t* A, const float* sa, const uint8_t* B, cons
         if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbRow, JET_BIG>, BigCfg::kLdsBytes);
         if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbBlock, JET_SMALL>, SmallCfg::kLdsBytes);
         if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbRow, JET_SMALL>, SmallCfg::kLdsBytes);
-        if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel, kSkinnyPass * kSkinnyGroupBytes);
+        if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel, kSkLdsBytes);
         attr_err = e;
     });
     if (attr_err != hipSuccess) return attr_err;
 
     uint16_t* o = static_cast<uint16_t*>(out);
     if (I <= 16 && sb_mode == kSbBlock) {
-        hipLaunchKernelGGL(gemm_skinny_kernel, dim3((unsigned)(J / 16)), dim3(512),
-                           kSkinnyPass * kSkinnyGroupBytes, st, A, sa, B, sb, o, (int)I, (int)J, (int)R);
+        hipLaunchKernelGGL(gemm_skinny_kernel, dim3((unsigned)(J / 16)), dim3(64 * kSkWaves), kSkLdsBytes,
+                           st, A, sa, B, sb, o, (int)I, (int)J, (int)R);
         return hipGetLastError();
     }
     if (sb_mode == kSbBlock) return launch_tile<kSbBlock>(A, sa, B, sb, o, I, J, R, st);
