@@ -8,6 +8,7 @@
 // depend on any other group, so kernels are free to compute the p_g of different
 // groups wherever they like; only the fma chain is ordered.  That keeps a token
 // row bit-identical between decode-shaped and training-shaped calls (Sec. 4.1).
+#include <algorithm>
 #include <mutex>
 
 #include "jet_internal.h"
@@ -57,10 +58,27 @@ __device__ __forceinline__ int xcd_contiguous_id(int b, int n) {
 
 // ------------------------------------------------------------------------
 // Tile kernel.  A workgroup of WI x WJ waves owns a BM x BN output tile
-// (BM = WI*TM*16, BN = WJ*TN*16); a wave owns TM x TN MFMA tiles.  The operand
-// tiles of one group (BM + BN rows x 128 bytes) go global->LDS directly in MFMA
-// whole cache lines, swizzled so that every fragment ds_read_b128 is conflict-free;
-// two stages, the copy of group g+1 runs under the MFMAs of group g.
+// (BM = WI*TM*16, BN = WJ*TN*16); a wave owns TM x TN MFMA tiles.  Workgroups are
+// persistent: each one walks a list of output tiles, and the (tile, group) pairs of
+// that list form one continuous stream of steps, so the copy engine, the LDS and the
+// matrix core never drain between tiles.
+//
+// Per step the operand tiles of one group (BM + BN rows x 128 bytes) go global->LDS
+// directly as whole cache lines, swizzled so that every fragment ds_read_b128 is
+// conflict-free.  Two LDS stages; step q lives in stage q & 1.
+//
+// Pipeline of one step q (t counts the wave's MFMA tiles, row m = t / TN, column n = t % TN):
+//   top      : the column fragments cf[0..TN), the first row fragment and the scales of
+//              step q are already in registers (fetched during step q-1)
+//   t < last row : MFMA stream; row fragment m+1 is fetched from stage q&1 while row m runs;
+//              the scale fmas of tile t-2 run on the VALU under the MFMA of tile t
+//   t = first tile of the last row : every LDS read of stage q&1 has returned.  Wait for this
+//              wave's copies of step q+1, workgroup barrier.  Now stage (q+1)&1 is complete
+//              and stage q&1 is free: start fetching step q+1's fragments (cf[n] right after the
+//              last MFMA that uses the old cf[n]) and start copying step q+2 into stage q&1.
+// The only barrier of a step therefore sits in the middle of the MFMA stream, the LDS
+// latency of the next step's first fragments hides under the last row of this step,
+// and every copy has about one whole step to land.
 //
 // LDS stage layout: [A tile BM*128][B tile BN*128][scales (BM+BN)*4]
 //   tile: 1 KB block per 8 rows, copied by one instruction that moves 8 whole 128-byte
@@ -70,8 +88,8 @@ __device__ __forceinline__ int xcd_contiguous_id(int b, int n) {
 //         (rows 0..15, same chunk) hit 16 different 16-byte bank groups: measured 6.4
 //         cycles per ds_read_b128 (160 B/clk/CU) against 16.4 for a plain row-major tile
 //   scales: wave w's 256 B = [sa rows 32w..32w+31][sb of columns 32w..32w+31]
-// Both configurations have BM = BN = 32 * waves, so every wave copies 4 A halves,
-// 4 B halves and one scale line per stage.
+// Both configurations have BM = BN = 32 * waves, so every wave copies 4 A blocks,
+// 4 B blocks and one scale line per step.
 // ------------------------------------------------------------------------
 template <int WI, int WJ, int TM, int TN>
 struct TileCfg {
@@ -82,8 +100,38 @@ struct TileCfg {
     static constexpr int kStageBytes = kABytes + kBBytes + (BM + BN) * 4;
     static constexpr int kStages = 2;
     static constexpr int kLdsBytes = kStages * kStageBytes;
+    static constexpr int kOccupancy = 512 / kThreads;   // workgroups per CU
     static_assert(BM == 32 * kWaves && BN == 32 * kWaves, "copy schedule assumes BM = BN = 32 * waves");
+    static_assert(TM % 2 == 0 && TN % 2 == 0, "fragment double buffer and paired stores assume even TM, TN");
 };
+
+// Tiles of one persistent workgroup.  The hardware deals workgroup b to XCD b % 8.  The
+// logical tile ids are split into 8 contiguous ranges, one per XCD, and the workgroups of
+// an XCD take the ids of their range round-robin, so that at any time the workgroups of
+// an XCD work on neighbouring ids (8 tile rows x a few tile columns: shared operands,
+// one L2).
+struct TileList {
+    int first, stride, count;   // ids first + k * stride, 0 <= k < count
+};
+__device__ __forceinline__ TileList tiles_of_workgroup(int b, int n_wg, int n_tiles) {
+    const int x = b & 7, j = b >> 3;
+    const int wgs_here = (n_wg - x + 7) >> 3;
+    const int q = n_tiles >> 3, rem = n_tiles & 7;
+    const int start = x * q + (x < rem ? x : rem), n_here = q + (x < rem ? 1 : 0);
+    TileList t;
+    t.first = start + j;
+    t.stride = wgs_here;
+    t.count = (j < n_here) ? (n_here - j + wgs_here - 1) / wgs_here : 0;
+    return t;
+}
+
+// two floats -> two bf16 (round to nearest even) in one dword, low half first
+__device__ __forceinline__ uint32_t bf16_pack2(float lo, float hi) {
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
 
 template <int SB_MODE, int WI, int WJ, int TM, int TN>
 __global__ __launch_bounds__(64 * WI * WJ, 512 / (64 * WI * WJ))
@@ -96,146 +144,244 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
     const int t = threadIdx.x, w = t >> 6, l = t & 63, r = l & 15, c4 = l >> 4;
     const int G = R / kGroup;
 
-    // workgroup -> tile: bands of 8 tile rows, walked column by column
-    const int lid = xcd_contiguous_id(blockIdx.x, gridDim.x);
-    constexpr int kBand = 8;
-    const int band = lid / (kBand * tiles_j);
-    const int within = lid - band * (kBand * tiles_j);
-    const int rows_in_band = min(kBand, tiles_i - band * kBand);
-    const int ti = band * kBand + within % rows_in_band;
-    const int tj = within / rows_in_band;
-    const int i0 = ti * C::BM, j0 = tj * C::BN;
+    const TileList mine = tiles_of_workgroup(blockIdx.x, gridDim.x, tiles_i * tiles_j);
+    if (mine.count == 0) return;                     // whole workgroup
+    const int n_steps = mine.count * G;
 
-    // copy schedule of this wave: A halves 4w..4w+3, B halves 4w..4w+3, one scale line
-    const uint8_t* baseA = A + (size_t)i0 * R;
-    const uint8_t* baseB = B + (size_t)j0 * R;
-    uint32_t offA[4], offB[4];
-#pragma unroll
-    for (int x = 0; x < 4; ++x) {
-        const int row = 32 * w + 8 * x + (l >> 3);             // row of the tile this lane copies
-        const int chunk = (l & 7) ^ ((row >> 1) & 7);
-        const int row_a = min(i0 + row, I - 1) - i0;           // rows past the end repeat the last one
-        offA[x] = (uint32_t)row_a * (uint32_t)R + 16 * chunk;
-        offB[x] = (uint32_t)row * (uint32_t)R + 16 * chunk;
-    }
-    // where this lane's two 16-byte pieces of a fragment (row r, chunks c4 and 4 + c4) sit
+    // logical id -> tile origin: bands of 8 tile rows, walked column by column
+    auto tile_origin = [&](int k, int& i0, int& j0) {
+        constexpr int kBand = 8;
+        const int lid = mine.first + k * mine.stride;
+        const int band = lid / (kBand * tiles_j);
+        const int within = lid - band * (kBand * tiles_j);
+        const int rows_in_band = min(kBand, tiles_i - band * kBand);
+        i0 = (band * kBand + within % rows_in_band) * C::BM;
+        j0 = (within / rows_in_band) * C::BN;
+    };
+
+    // ---- copy cursor: the step whose operand tiles are being copied ----
+    // copy schedule of this wave: A blocks 4w..4w+3, B blocks 4w..4w+3, one scale line.
+    // Block c holds tile rows 32w + 8c .. + 7; lane l copies 16 bytes of row 32w + 8c + (l>>3):
+    // chunk (l&7) ^ swizzle(row), swizzle = (row>>1)&7 = (l>>4) | ((c&1)<<2).
+    struct Cursor {
+        const uint8_t *baseA, *baseB;   // tile origins (wave-uniform)
+        const float* gs;                // this lane's scale row
+        int k, g, rows;                 // tile in the list, group, valid A rows of the tile
+    };
+    const uint32_t lane_row = 32 * w + (l >> 3);
+    const uint32_t lane_chunk = 16 * ((l & 7) ^ (l >> 4));
+    auto cursor_at_tile = [&](int k) {
+        int i0, j0;
+        tile_origin(k, i0, j0);
+        Cursor c;
+        c.baseA = static_cast<const uint8_t*>(uniform_ptr(A + (size_t)i0 * R));
+        c.baseB = static_cast<const uint8_t*>(uniform_ptr(B + (size_t)j0 * R));
+        c.k = k;
+        c.g = 0;
+        c.rows = I - i0;
+        if (l < 32) {
+            c.gs = sa + (size_t)min(i0 + 32 * w + l, I - 1) * G;
+        } else if (SB_MODE == kSbBlock) {
+            c.gs = sb + (size_t)((j0 + 32 * w + (l - 32)) >> 7) * G;
+        } else {
+            c.gs = sb + (size_t)(j0 + 32 * w + (l - 32)) * G;
+        }
+        return c;
+    };
+    // the step after c; past the end of the list the cursor stays on the last step (its
+    // tiles are then copied again into a stage nobody reads: harmless, and branch-free)
+    auto cursor_after = [&](const Cursor& c) {
+        Cursor n = c;
+        if (c.g + 1 < G) n.g = c.g + 1;
+        else if (c.k + 1 < mine.count) n = cursor_at_tile(c.k + 1);
+        return n;
+    };
+    const uint32_t ldsw = __builtin_amdgcn_readfirstlane(lds0 + 4 * w * 1024);
+    const uint32_t ldss = __builtin_amdgcn_readfirstlane(lds0 + C::kABytes + C::kBBytes + w * 256);
+    constexpr int kCopies = 9;
+    // copy i (0..8) of step c into stage `slot`: A blocks, B blocks, scale line
+    auto copy_one = [&](const Cursor& c, int i, int slot) {
+        const uint32_t st = slot * C::kStageBytes;
+        if (i < 4) {
+            // rows past the end of A repeat the last valid one (their outputs are never stored)
+            const uint32_t row = min(lane_row + 8 * i, (uint32_t)(c.rows - 1));
+            const uint32_t off = row * (uint32_t)R + (lane_chunk ^ ((i & 1) * 64));
+            dma16(ldsw + st + i * 1024, c.baseA + (size_t)c.g * kGroup, off);
+        } else if (i < 8) {
+            const uint32_t off = lane_row * (uint32_t)R + (lane_chunk ^ ((i & 1) * 64));
+            dma16(ldsw + st + C::kABytes + (i - 4) * 1024,
+                  c.baseB + (size_t)c.g * kGroup + (size_t)(8 * (i - 4)) * R, off);
+        } else {
+            dma4(ldss + st, c.gs + c.g);
+        }
+    };
+
+    // ---- fragment addressing ----
+    const int wi = w / WJ, wj = w % WJ;
+    // this lane's two 16-byte pieces of a fragment (row r, chunks c4 and 4 + c4)
     const int swz = (r >> 1) & 7;
     const int frag_lo = (r >> 3) * 1024 + (r & 7) * 128 + 16 * (c4 ^ swz);
     const int frag_hi = (r >> 3) * 1024 + (r & 7) * 128 + 16 * ((4 + c4) ^ swz);
-    const float* gs;
-    if (l < 32) {
-        gs = sa + (size_t)min(i0 + 32 * w + l, I - 1) * G;
-    } else if (SB_MODE == kSbBlock) {
-        gs = sb + (size_t)((j0 + 32 * w + (l - 32)) >> 7) * G;
-    } else {
-        gs = sb + (size_t)(j0 + 32 * w + (l - 32)) * G;
-    }
-    const uint32_t ldsw = __builtin_amdgcn_readfirstlane(lds0 + 4 * w * 1024);
-    const uint32_t ldss = __builtin_amdgcn_readfirstlane(lds0 + C::kABytes + C::kBBytes + w * 256);
-
-    // copy k (0..8) of this wave for group g into stage `slot`: A blocks, B blocks, scale line
-    auto issue_one = [&](int k, int g, int slot) {
-        const uint32_t st = slot * C::kStageBytes;
-        if (k < 4) dma16(ldsw + st + k * 1024, baseA + (size_t)g * kGroup, offA[k]);
-        else if (k < 8) dma16(ldsw + st + C::kABytes + (k - 4) * 1024, baseB + (size_t)g * kGroup, offB[k - 4]);
-        else dma4(ldss + st, gs + g);
+    auto row_frag = [&](int slot, int m) {
+        const uint8_t* p = smem + slot * C::kStageBytes + (wi * TM + m) * 2048;
+        return load_frag(p + frag_lo, p + frag_hi);
     };
-    constexpr int kCopies = 9;
+    auto col_frag = [&](int slot, int n) {
+        const uint8_t* p = smem + slot * C::kStageBytes + C::kABytes + (wj * TN + n) * 2048;
+        return load_frag(p + frag_lo, p + frag_hi);
+    };
+    // scales of a step as the lane needs them: sa of its row in each of the TM row tiles and
+    // the scale(s) of its columns
+    // (the per-column scales of WGrad are fetched at the top of the step instead: the
+    // first fma needs them two MFMAs later, and there are no registers to hold them early)
+    struct RawScales {
+        float a[TM];
+        float b_block;
+    };
+    auto load_scales = [&](int slot, RawScales& s) {
+        const uint8_t* sc = smem + slot * C::kStageBytes + C::kABytes + C::kBBytes;
+#pragma unroll
+        for (int m = 0; m < TM; ++m) {
+            const int ii = (wi * TM + m) * 16 + r;
+            s.a[m] = *reinterpret_cast<const float*>(sc + (ii >> 5) * 256 + (ii & 31) * 4);
+        }
+        if (SB_MODE == kSbBlock) {
+            const int jj = wj * TN * 16;   // the wave's columns share one 128-wide block
+            s.b_block = *reinterpret_cast<const float*>(sc + (jj >> 5) * 256 + 128 + (jj & 31) * 4);
+        }
+    };
+    auto load_col_scales = [&](int slot, v4f (&s)[TN]) {
+        const uint8_t* sc = smem + slot * C::kStageBytes + C::kABytes + C::kBBytes;
+#pragma unroll
+        for (int n = 0; n < TN; ++n) {
+            const int jj = (wj * TN + n) * 16 + 4 * c4;
+            s[n] = *reinterpret_cast<const v4f*>(sc + (jj >> 5) * 256 + 128 + (jj & 31) * 4);
+        }
+    };
 
-    const int wi = w / WJ, wj = w % WJ;
+    constexpr int kTiles = TM * TN, kLag = 2;
+    // The scale fmas of tile t-2 run next to the MFMA of tile t, far enough behind their own
+    // MFMA that its result needs no wait.  FProp/DGrad: MFMA first, three result buffers.
+    // WGrad (twice the VALU work, 16 more registers of column scales): fmas first, two buffers.
+    constexpr bool kFmaFirst = (SB_MODE != kSbBlock);
+    constexpr int kRing = kFmaFirst ? 2 : 3;
+    constexpr int kSync = (TM - 1) * TN;                 // first tile of the last row
+    constexpr int kLate = kTiles + kLag - 1 - kSync;     // copies issued after the barrier of a step
+    static_assert(kLate >= 1 && kLate <= kCopies && kCopies - kLate <= kSync, "copy slots");
+
+    // ---- prologue: step 0 into stage 0, first copies of step 1, fragments of step 0 ----
+    Cursor cur = cursor_at_tile(0);
+#pragma unroll
+    for (int i = 0; i < kCopies; ++i) copy_one(cur, i, 0);
+    cur = cursor_after(cur);
+    JET_WAIT_VMCNT(0);
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int i = 0; i < kLate; ++i) copy_one(cur, i, 1);
+
+    v8i cf[TN], xf[2];
+    RawScales next;
+#pragma unroll
+    for (int n = 0; n < TN; ++n) cf[n] = col_frag(0, n);
+    xf[0] = row_frag(0, 0);
+    load_scales(0, next);
+
     v4f acc[TM][TN];
 #pragma unroll
     for (int a = 0; a < TM; ++a)
 #pragma unroll
         for (int b = 0; b < TN; ++b) acc[a][b] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
 
-#pragma unroll
-    for (int k = 0; k < kCopies; ++k) issue_one(k, 0, 0);
-    for (int g = 0; g < G; ++g) {
-        JET_WAIT_VMCNT(0);               // this wave's share of group g has landed
-        __builtin_amdgcn_s_barrier();    // ... and everybody else's; slot (g+1)&1 is free
-        asm volatile("" ::: "memory");
-        const int gn = min(g + 1, G - 1);
+    // `cur` is the cursor of step q+1 at the top of step q
+    for (int q = 0, k = 0, g = 0; q < n_steps; ++q) {
+        const int slot = q & 1;
+        const Cursor after = cursor_after(cur);     // step q+2 (all control flow of a step is here)
 
-        const uint8_t* st = smem + (g & 1) * C::kStageBytes;
-        const uint8_t* sc = st + C::kABytes + C::kBBytes;
-        v8i cf[TN];
-#pragma unroll
-        for (int n = 0; n < TN; ++n) {
-            const uint8_t* p = st + C::kABytes + (wj * TN + n) * 2048;
-            cf[n] = load_frag(p + frag_lo, p + frag_hi);
-        }
+        // ---- one straight-line block from here to the end of the tile loop ----
+        // scales of this step: s = sa * sb, one binary32 product per (row, column scale)
         float sai[TM];
-#pragma unroll
-        for (int m = 0; m < TM; ++m) {
-            const int ii = (wi * TM + m) * 16 + r;
-            sai[m] = *reinterpret_cast<const float*>(sc + (ii >> 5) * 256 + (ii & 31) * 4);
-        }
         v4f sbj[TN];
-        if (SB_MODE == kSbBlock) {
-            const int jj = wj * TN * 16;   // the wave's columns share one 128-wide block
-            const float sbv = *reinterpret_cast<const float*>(sc + (jj >> 5) * 256 + 128 + (jj & 31) * 4);
 #pragma unroll
-            for (int m = 0; m < TM; ++m) sai[m] *= sbv;
-        } else {
-#pragma unroll
-            for (int n = 0; n < TN; ++n) {
-                const int jj = (wj * TN + n) * 16 + 4 * c4;
-                sbj[n] = *reinterpret_cast<const v4f*>(sc + (jj >> 5) * 256 + 128 + (jj & 31) * 4);
-            }
-        }
-        // Software pipeline over the TM x TN MFMA tiles of this wave, t = m*TN + n: the matrix
-        // core works on tile t while the VALU runs the scale fmas of tile t-2 and LDS delivers
-        // the row fragment of the next m.  The nine copies of the next group are slipped in
-        // one at a time between tiles, so the vector-memory queue never holds up the MFMA
-        // stream.  (After the last group the copy re-reads it into the idle stage.)
-        constexpr int kTiles = TM * TN, kLag = 2, kRing = 3;
-        constexpr int kCopyEvery = (kTiles >= 2 * kCopies) ? 2 : 1;
-        v8i xf[2];
+        for (int m = 0; m < TM; ++m) sai[m] = (SB_MODE == kSbBlock) ? next.a[m] * next.b_block : next.a[m];
+        if (SB_MODE != kSbBlock) load_col_scales(slot, sbj);
+
         v4f pr[kRing];
-        xf[0] = load_frag(st + (wi * TM) * 2048 + frag_lo, st + (wi * TM) * 2048 + frag_hi);
 #pragma unroll
         for (int t = 0; t < kTiles + kLag; ++t) {
-            if (t < kTiles) {
-                const int m = t / TN, n = t % TN;
-                if (n == 0 && m + 1 < TM) {
-                    const uint8_t* p = st + (wi * TM + m + 1) * 2048;
-                    xf[(m + 1) & 1] = load_frag(p + frag_lo, p + frag_hi);
-                }
-                pr[t % kRing] = group_product(cf[n], xf[m & 1]);
-            }
-            if (t >= kLag) {
+            auto scale_fmas = [&]() {
+                if (t < kLag) return;
                 const int u = t - kLag, m = u / TN, n = u % TN;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const float s = (SB_MODE == kSbBlock) ? sai[m] : sai[m] * sbj[n][e];
                     acc[m][n][e] = chain(pr[u % kRing][e], s, acc[m][n][e]);
                 }
+            };
+            if (kFmaFirst) {
+                scale_fmas();
+                __builtin_amdgcn_sched_barrier(0);
             }
+            if (t < kTiles) {
+                const int m = t / TN, n = t % TN;
+                if (n == 0 && m + 1 < TM) xf[(m + 1) & 1] = row_frag(slot, m + 1);
+                pr[t % kRing] = group_product(cf[n], xf[m & 1]);
+            }
+            if (!kFmaFirst) scale_fmas();
             __builtin_amdgcn_sched_barrier(0);
-            if (t % kCopyEvery == kCopyEvery - 1 && t / kCopyEvery < kCopies) {
-                issue_one(t / kCopyEvery, gn, (g + 1) & 1);
+            if (t == kSync) {
+                // every read of stage `slot` has returned (the MFMA above needed the last one);
+                // this wave's copies of step q+1 were issued about one step ago
+                JET_WAIT_VMCNT(0);
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                cur = after;                          // step q+2 goes into stage `slot`
+                xf[TM & 1] = row_frag(slot ^ 1, 0);   // TM even: the buffer the last row does not use
+                load_scales(slot ^ 1, next);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (t >= kSync && t < kTiles) {
+                cf[t - kSync] = col_frag(slot ^ 1, t - kSync);   // its last MFMA of this step is issued
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (t > kSync) {
+                copy_one(cur, t - kSync - 1, slot);   // copies 0 .. kLate-1 of step q+2
+                __builtin_amdgcn_sched_barrier(0);
+            } else if (t < kCopies - kLate) {
+                copy_one(cur, kLate + t, slot ^ 1);   // remaining copies of step q+1
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-    }
-    JET_WAIT_VMCNT(0);   // the last (redundant) copies must land before the LDS is released
+        if (++g < G) continue;
+        g = 0;
 
-    // epilogue: a lane holds 4 consecutive columns of one row per MFMA tile
+        // epilogue of tile k.  A lane holds row r, columns 4 c4 .. 4 c4 + 3 of each MFMA tile;
+        // two row-swaps between neighbouring column tiles give every lane 8 consecutive
+        // columns (16 bytes) and every row 64 contiguous bytes per store instruction.
+        int i0, j0;
+        tile_origin(k, i0, j0);
 #pragma unroll
-    for (int m = 0; m < TM; ++m) {
-        const int i = i0 + (wi * TM + m) * 16 + r;
-        if (i < I) {
+        for (int m = 0; m < TM; ++m) {
+            const int i = i0 + (wi * TM + m) * 16 + r;
 #pragma unroll
-            for (int n = 0; n < TN; ++n) {
-                const int j = j0 + (wj * TN + n) * 16 + 4 * c4;
-                uint2 o;
-                o.x = bf16_rne(acc[m][n][0]) | (bf16_rne(acc[m][n][1]) << 16);
-                o.y = bf16_rne(acc[m][n][2]) | (bf16_rne(acc[m][n][3]) << 16);
-                *reinterpret_cast<uint2*>(out + (size_t)i * J + j) = o;
+            for (int n = 0; n < TN; n += 2) {
+                const uint32_t a0 = bf16_pack2(acc[m][n][0], acc[m][n][1]);
+                const uint32_t a1 = bf16_pack2(acc[m][n][2], acc[m][n][3]);
+                const uint32_t b0 = bf16_pack2(acc[m][n + 1][0], acc[m][n + 1][1]);
+                const uint32_t b1 = bf16_pack2(acc[m][n + 1][2], acc[m][n + 1][3]);
+                // lanes 16-31 and 48-63 of the first operand <-> lanes 0-15 and 32-47 of the second
+                const auto s0 = __builtin_amdgcn_permlane16_swap(a0, b0, false, false);
+                const auto s1 = __builtin_amdgcn_permlane16_swap(a1, b1, false, false);
+                const uint4 o = {s0[0], s1[0], s0[1], s1[1]};
+                const int j = j0 + (wj * TN + n + (c4 & 1)) * 16 + (c4 >> 1) * 8;
+                if (i < I) *reinterpret_cast<uint4*>(out + (size_t)i * J + j) = o;
+                acc[m][n] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+                acc[m][n + 1] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
             }
         }
+        ++k;
     }
+    JET_WAIT_VMCNT(0);   // nothing may be in flight towards the LDS when it is released
 }
 
 // ------------------------------------------------------------------------
@@ -364,16 +510,20 @@ using SmallCfg = TileCfg<JET_SMALL>;
 template <int SB_MODE>
 static hipError_t launch_tile(const uint8_t* A, const float* sa, const uint8_t* B, const float* sb,
                               uint16_t* o, long I, long J, long R, hipStream_t st) {
-    // shape-only choice: the big tile when it divides J and fills the 256 CUs
+    // shape-only choice: the big tile when it divides J and fills the 256 CUs.  The grid
+    // is persistent: at most one resident set of workgroups, each walking its tile list.
+    const int cus = 256;
     const long big_tiles = ((I + 255) / 256) * (J / 256);
     if (J % 256 == 0 && big_tiles >= 224) {
         const int ti = (int)((I + 255) / 256), tj = (int)(J / 256);
-        hipLaunchKernelGGL((gemm_tile_kernel<SB_MODE, JET_BIG>), dim3((unsigned)(ti * tj)),
+        const long wgs = std::min<long>((long)ti * tj, (long)cus * BigCfg::kOccupancy);
+        hipLaunchKernelGGL((gemm_tile_kernel<SB_MODE, JET_BIG>), dim3((unsigned)wgs),
                            dim3(BigCfg::kThreads), BigCfg::kLdsBytes, st, A, sa, B, sb, o, (int)I, (int)J,
                            (int)R, ti, tj);
     } else {
         const int ti = (int)((I + 127) / 128), tj = (int)(J / 128);
-        hipLaunchKernelGGL((gemm_tile_kernel<SB_MODE, JET_SMALL>), dim3((unsigned)(ti * tj)),
+        const long wgs = std::min<long>((long)ti * tj, (long)cus * SmallCfg::kOccupancy);
+        hipLaunchKernelGGL((gemm_tile_kernel<SB_MODE, JET_SMALL>), dim3((unsigned)wgs),
                            dim3(SmallCfg::kThreads), SmallCfg::kLdsBytes, st, A, sa, B, sb, o, (int)I,
                            (int)J, (int)R, ti, tj);
     }
