@@ -493,6 +493,235 @@ __global__ __launch_bounds__(64 * kSkWaves) void gemm_skinny_kernel(const uint8_
     if (r < I) out[(size_t)r * J + j0 + 4 * c4 + w] = (uint16_t)bf16_rne(acc);
 }
 
+// ------------------------------------------------------------------------
+// Strip kernel for decode batches, 16 < I <= 256 (block scales only).  The weights are
+// streamed once per 64-row block of the batch, so the kernel lives on memory-level
+// parallelism, not on the matrix core.  A workgroup of 4 waves (one per SIMD) owns a
+// (16 RM) x (16 CN) output tile and walks the whole reduction two groups (a "pair") at
+// a time.  The weight rows (from HBM) and the activation rows + scales (L2-resident)
+// travel global->LDS through two separate rings, a deep one for the weights and a
+// shallower one for the activations.  The outstanding-copy counter of a wave retires in
+// issue order, so a wave that issued both streams could never keep the weights further
+// ahead than the activations: waves 0 and 1 copy only weights, waves 2 and 3 only
+// activations and scales.  One barrier per pair; the fragments of pair p+2 are fetched from
+// LDS into registers while pair p is computed, so neither the LDS latency nor the barrier
+// is paid per group.  Wave w owns RM*CN/4 of the MFMA tiles and runs their ordered fma
+// chains in registers: the same chain as every other kernel, so rows are bit-identical.
+// ------------------------------------------------------------------------
+template <int RM, int CN, int WDEPTH, int ADEPTH>
+struct StripCfg {
+    static constexpr int kWaves = 4;
+    static constexpr int BM = 16 * RM, BN = 16 * CN;
+    static constexpr int kWDepth = WDEPTH, kADepth = ADEPTH;    // ring depths in pairs
+    static constexpr int kWGroup = CN * 2048;                   // weight fragments of a group
+    static constexpr int kAGroup = RM * 2048 + 1024;            // activation fragments, sa[64] at +0, sb at +512
+    static constexpr int kWStage = 2 * kWGroup, kAStage = 2 * kAGroup;
+    static constexpr int kSinkBytes = 256;                      // landing zone of the L2 warm-up loads
+    static constexpr int kLdsBytes = kWDepth * kWStage + kADepth * kAStage + kSinkBytes;
+    static constexpr int kWOps = 2 * CN, kAOps = 2 * (RM + 1);  // copies per wave per pair
+    static constexpr int kTiles = RM * CN / kWaves;             // MFMA tiles per wave
+    static constexpr int kNM = (kTiles + CN - 1) / CN;          // distinct row tiles per wave
+    static constexpr int kNN = kTiles < CN ? kTiles : CN;       // distinct column tiles per wave
+    static constexpr int kFetchOps = 2 * (2 * (kNM + kNN) + kNM + 1);   // LDS reads of one pair
+    static_assert(RM % 2 == 0 && CN % 2 == 0 && RM * CN % kWaves == 0 && BM <= 64 && 128 % BN == 0, "");
+    static_assert(kNM * kNN == kTiles, "a wave's tiles form a kNM x kNN rectangle");
+    static_assert(kWDepth >= 4 && kADepth >= 4 && (kWDepth - 3) * kWOps < 64 && (kADepth - 3) * kAOps < 64, "");
+    static_assert(kLdsBytes <= 160 * 1024, "");
+};
+
+template <int RM, int CN, int WDEPTH, int ADEPTH>
+__global__ __launch_bounds__(256) void gemm_strip_kernel(const uint8_t* __restrict__ A,
+                                                          const float* __restrict__ sa,
+                                                          const uint8_t* __restrict__ B,
+                                                          const float* __restrict__ sb,
+                                                          uint16_t* __restrict__ out, int I, int J, int R,
+                                                          int row_blocks) {
+    using C = StripCfg<RM, CN, WDEPTH, ADEPTH>;
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_ptr_t)smem;
+    const int t = threadIdx.x, w = __builtin_amdgcn_readfirstlane(t >> 6), l = t & 63, r = l & 15, c4 = l >> 4;
+    const int G = R / kGroup, P = (G + 1) / 2;
+
+    // workgroups that share a weight strip (different row blocks) sit next to each other on
+    // one XCD, so the strip leaves HBM once
+    const int strips = J / C::BN, b = blockIdx.x;
+    int rb, strip;
+    if (strips % 8 == 0) {
+        rb = (b >> 3) % row_blocks;
+        strip = ((b >> 3) / row_blocks) * 8 + (b & 7);
+    } else {
+        rb = b % row_blocks;
+        strip = b / row_blocks;
+    }
+    const int i0 = rb * C::BM, j0 = strip * C::BN;
+
+    // ---- copies: a wave copies kMine consecutive 1 KB blocks (8 rows) of each group of a
+    // pair; block b is half b & 1 of fragment b >> 1 ----
+    const bool w_stream = w < 2;
+    const int side = w & 1;
+    constexpr int kWMine = CN, kAMine = RM;
+    constexpr int kMineMax = RM > CN ? RM : CN;
+    const uint32_t lane_chunk = 16 * ((l & 7) ^ (l >> 4));
+    const uint8_t* baseW = static_cast<const uint8_t*>(uniform_ptr(B + (size_t)j0 * R));
+    const uint8_t* baseA = static_cast<const uint8_t*>(uniform_ptr(A + (size_t)i0 * R));
+    uint32_t off[kMineMax];
+#pragma unroll
+    for (int i = 0; i < kMineMax; ++i) {
+        if (w_stream) {
+            const int blk = side * kWMine + (i < kWMine ? i : 0);
+            off[i] = (uint32_t)(8 * blk + (l >> 3)) * (uint32_t)R + (lane_chunk ^ ((blk & 1) * 64));
+        } else {
+            const int blk = side * kAMine + (i < kAMine ? i : 0);
+            const int row = min(i0 + 8 * blk + (l >> 3), I - 1) - i0;   // rows past the end repeat the last one
+            off[i] = (uint32_t)row * (uint32_t)R + (lane_chunk ^ ((blk & 1) * 64));
+        }
+    }
+    // scale line: wave 2 copies sa of the tile's rows (up to 64), wave 3 the block scale
+    const float* gs = (w == 2) ? sa + (size_t)min(i0 + l, I - 1) * G : sb + (size_t)(j0 >> 7) * G;
+    const uint32_t lds_w = __builtin_amdgcn_readfirstlane(lds0 + side * kWMine * 1024);
+    const uint32_t lds_a = __builtin_amdgcn_readfirstlane(lds0 + C::kWDepth * C::kWStage + side * kAMine * 1024);
+    const uint32_t lds_s = __builtin_amdgcn_readfirstlane(lds0 + C::kWDepth * C::kWStage + RM * 2048 + side * 512);
+    // this wave's copies of pair p (groups past the end repeat the last one)
+    auto issue = [&](int p) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int g = min(2 * p + h, G - 1);
+            if (w_stream) {
+                const uint32_t st = (p % C::kWDepth) * C::kWStage + h * C::kWGroup;
+#pragma unroll
+                for (int i = 0; i < kWMine; ++i) dma16(lds_w + st + i * 1024, baseW + (size_t)g * kGroup, off[i]);
+            } else {
+                const uint32_t st = (p % C::kADepth) * C::kAStage + h * C::kAGroup;
+#pragma unroll
+                for (int i = 0; i < kAMine; ++i) dma16(lds_a + st + i * 1024, baseA + (size_t)g * kGroup, off[i]);
+                dma4(lds_s + st, gs + g);
+            }
+        }
+    };
+
+    // ---- this wave's MFMA tiles: rows m0 .. m0+kNM-1, columns n0 .. n0+kNN-1 (in tiles) ----
+    const int first = w * C::kTiles, m0 = first / CN, n0 = first % CN;
+    const int swz = (r >> 1) & 7;
+    const int frag_lo = (r >> 3) * 1024 + (r & 7) * 128 + 16 * (c4 ^ swz);
+    const int frag_hi = (r >> 3) * 1024 + (r & 7) * 128 + 16 * ((4 + c4) ^ swz);
+    struct Operands {           // of one pair
+        v8i wf[2][C::kNN], xf[2][C::kNM];
+        float sa[2][C::kNM], sb[2];
+    };
+    auto fetch = [&](int p, Operands& o) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint8_t* pw = smem + (p % C::kWDepth) * C::kWStage + h * C::kWGroup;
+            const uint8_t* pa = smem + C::kWDepth * C::kWStage + (p % C::kADepth) * C::kAStage + h * C::kAGroup;
+#pragma unroll
+            for (int n = 0; n < C::kNN; ++n)
+                o.wf[h][n] = load_frag(pw + (n0 + n) * 2048 + frag_lo, pw + (n0 + n) * 2048 + frag_hi);
+#pragma unroll
+            for (int m = 0; m < C::kNM; ++m) {
+                o.xf[h][m] = load_frag(pa + (m0 + m) * 2048 + frag_lo, pa + (m0 + m) * 2048 + frag_hi);
+                o.sa[h][m] = *reinterpret_cast<const float*>(pa + RM * 2048 + ((m0 + m) * 16 + r) * 4);
+            }
+            o.sb[h] = *reinterpret_cast<const float*>(pa + RM * 2048 + 512);
+        }
+    };
+    v4f acc[C::kNM][C::kNN];
+#pragma unroll
+    for (int m = 0; m < C::kNM; ++m)
+#pragma unroll
+        for (int n = 0; n < C::kNN; ++n) acc[m][n] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+    auto compute = [&](int p, const Operands& o) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            if (2 * p + h >= G) break;               // odd G: the last pair has one group
+#pragma unroll
+            for (int m = 0; m < C::kNM; ++m) {
+                const float s = o.sa[h][m] * o.sb[h];
+#pragma unroll
+                for (int n = 0; n < C::kNN; ++n) {
+                    const v4f pg = group_product(o.wf[h][n], o.xf[h][m]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[m][n][e] = chain(pg[e], s, acc[m][n][e]);
+                }
+            }
+        }
+    };
+    // "my copies of all pairs up to the one issued `back` issue() calls ago have landed"
+    auto wait_copies = [&](int back) {
+        if (w_stream) {
+            if (back == C::kWDepth - 3) JET_WAIT_VMCNT((C::kWDepth - 3) * C::kWOps);
+            else if (back == C::kWDepth - 2) JET_WAIT_VMCNT((C::kWDepth - 2) * C::kWOps);
+            else JET_WAIT_VMCNT(0);
+        } else {
+            if (back == C::kWDepth - 3) JET_WAIT_VMCNT((C::kADepth - 3) * C::kAOps);
+            else if (back == C::kWDepth - 2) JET_WAIT_VMCNT((C::kADepth - 2) * C::kAOps);
+            else JET_WAIT_VMCNT(0);
+        }
+    };
+
+    // ---- L2 warm-up of this row block's activations ----
+    // Every workgroup of an XCD walks the same activation rows group by group at about the
+    // same time, so without help each group's copy would be a fresh miss to HBM.  The
+    // workgroups of an XCD touch one dword of every cache line once, up front, sharing the
+    // lines between them; the ring copies then hit in the L2.
+    {
+        const int per_xcd = (gridDim.x + 7) >> 3, me = b >> 3;
+        const int rows = min(C::BM, I - i0);
+        const long lines = (long)rows * G;
+        const uint32_t sink = __builtin_amdgcn_readfirstlane(lds0 + C::kWDepth * C::kWStage + C::kADepth * C::kAStage);
+        for (long x = (long)me * 256 + t; x < lines; x += (long)per_xcd * 256) {
+            const long row = x / G, g = x - row * G;
+            dma4(sink, reinterpret_cast<const float*>(baseA + (size_t)row * R + (size_t)g * kGroup));
+        }
+    }
+
+    // ---- prologue: fill both rings, fetch pairs 0 and 1 ----
+    // iteration p of the main loop issues pair p + depth; the prologue issues pairs 0 .. depth-1
+    // in the same relative order, so the steady-state counts hold from the start
+    for (int v = 0; v < C::kWDepth; ++v)
+        if (w_stream || v < C::kADepth) issue(v);
+    wait_copies(C::kWDepth - 2);                     // pairs 0 and 1 landed: depth-2 later pairs outstanding
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    Operands op[3];
+    fetch(0, op[0]);
+    fetch(min(1, P - 1), op[1]);
+
+    // iteration p: pairs <= p+2 have landed; slot of pair p is free (its fragments are in registers)
+    auto iteration = [&](int p, const Operands& cur, Operands& nxt2) {
+        wait_copies(C::kWDepth - 3);
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        issue(p + (w_stream ? C::kWDepth : C::kADepth));
+        fetch(min(p + 2, P - 1), nxt2);
+        compute(p, cur);
+        // my reads of pair p+1's slots are done before the next barrier lets them be overwritten
+        // (LDS reads return in order: at most the reads of pair p+2 stay outstanding)
+        __builtin_amdgcn_s_waitcnt(0xc07f | ((C::kFetchOps < 15 ? C::kFetchOps : 15) << 8));
+    };
+    int p = 0;
+    for (; p + 2 < P; p += 3) {
+        iteration(p, op[0], op[2]);
+        iteration(p + 1, op[1], op[0]);
+        iteration(p + 2, op[2], op[1]);
+    }
+    if (p < P) iteration(p, op[0], op[2]);
+    if (p + 1 < P) iteration(p + 1, op[1], op[0]);
+    JET_WAIT_VMCNT(0);   // nothing may be in flight towards the LDS when it is released
+
+#pragma unroll
+    for (int m = 0; m < C::kNM; ++m) {
+        const int i = i0 + (m0 + m) * 16 + r;
+#pragma unroll
+        for (int n = 0; n < C::kNN; ++n) {
+            const int j = j0 + (n0 + n) * 16 + 4 * c4;
+            uint2 o;
+            o.x = bf16_pack2(acc[m][n][0], acc[m][n][1]);
+            o.y = bf16_pack2(acc[m][n][2], acc[m][n][3]);
+            if (i < I) *reinterpret_cast<uint2*>(out + (size_t)i * J + j) = o;
+        }
+    }
+}
+
 // ----------------------------------------------------------------- launch --
 
 template <typename K>
@@ -504,6 +733,10 @@ static hipError_t allow_lds(K kernel, int bytes) {
 // big tile: 256x256, 8 waves of 128x64;  small tile: 128x128, 4 waves of 64x64
 #define JET_BIG 2, 4, 8, 4
 #define JET_SMALL 2, 2, 4, 4
+#define JET_STRIP_SMALL 2, 2, 8, 5   /* batches up to 32 rows */
+#define JET_STRIP_WIDE 4, 2, 7, 5    /* 64-row blocks */
+using StripSmall = StripCfg<JET_STRIP_SMALL>;
+using StripWide = StripCfg<JET_STRIP_WIDE>;
 using BigCfg = TileCfg<JET_BIG>;
 using SmallCfg = TileCfg<JET_SMALL>;
 
@@ -540,6 +773,8 @@ hipError_t launch_gemm(const uint8_t* A, const float* sa, const uint8_t* B, cons
         if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbBlock, JET_SMALL>, SmallCfg::kLdsBytes);
         if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbRow, JET_SMALL>, SmallCfg::kLdsBytes);
         if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel, kSkLdsBytes);
+        if (e == hipSuccess) e = allow_lds(gemm_strip_kernel<JET_STRIP_SMALL>, StripSmall::kLdsBytes);
+        if (e == hipSuccess) e = allow_lds(gemm_strip_kernel<JET_STRIP_WIDE>, StripWide::kLdsBytes);
         attr_err = e;
     });
     if (attr_err != hipSuccess) return attr_err;
@@ -548,6 +783,18 @@ hipError_t launch_gemm(const uint8_t* A, const float* sa, const uint8_t* B, cons
     if (I <= 16 && sb_mode == kSbBlock) {
         hipLaunchKernelGGL(gemm_skinny_kernel, dim3((unsigned)(J / 16)), dim3(64 * kSkWaves), kSkLdsBytes,
                            st, A, sa, B, sb, o, (int)I, (int)J, (int)R);
+        return hipGetLastError();
+    }
+    if (I <= 256 && sb_mode == kSbBlock) {
+        // decode batches: 32- or 64-row blocks x 32-column strips
+        if (I <= 32) {
+            hipLaunchKernelGGL((gemm_strip_kernel<JET_STRIP_SMALL>), dim3((unsigned)(J / 32)), dim3(256),
+                               StripSmall::kLdsBytes, st, A, sa, B, sb, o, (int)I, (int)J, (int)R, 1);
+        } else {
+            const int rbs = (int)((I + 63) / 64);
+            hipLaunchKernelGGL((gemm_strip_kernel<JET_STRIP_WIDE>), dim3((unsigned)(rbs * (J / 32))), dim3(256),
+                               StripWide::kLdsBytes, st, A, sa, B, sb, o, (int)I, (int)J, (int)R, rbs);
+        }
         return hipGetLastError();
     }
     if (sb_mode == kSbBlock) return launch_tile<kSbBlock>(A, sa, B, sb, o, I, J, R, st);
