@@ -26,6 +26,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_FP8_TFLOPS = 5000.0     # MI355X dense FP8 MFMA peak
+# HBM-side bytes per average FProp/DGrad launch of this workload, from two rocprofv3 --pmc runs of
+# this script (FETCH_SIZE x 2.000 KiB, WRITE_SIZE x 1.000 KiB per count; the factors are what the
+# counters read for a plain 1 GiB copy): profiles/bench_8B_M16384_hbm_counters.txt
+TILE_GEMM_TRAFFIC_BYTES = (371213.7 * 2.0 + 187525.9 * 1.0) * 1024.0
 PEAK_HBM_GBPS = 8000.0
 M_TRAIN = 16384
 DECODE_M = (1, 8, 32, 128)
@@ -152,6 +156,9 @@ def main():
         return tot_w / tot_t, tot_t / len(events), tot_w / len(events)
 
     g_rate, g_avg_s, g_avg_fl = rate(gemm_events)
+    # operands read once + bf16 output written once, per average FProp/DGrad launch
+    tile_alg_bytes = sum((M * K + M * N) * (1 + 4 / 128) + 2 * (N * K + 4 * (N // 128) * (K // 128))
+                         + 2 * M * N + 2 * M * K for _, N, K in layer) / (2 * len(layer))
     w_rate, w_avg_s, _ = rate(wgrad_events)
     q_rate, _, _ = rate(quant_events)
     gemm_time = sum(a.elapsed_time(b) for a, b, _ in gemm_events + wgrad_events) * 1e-3 / args.steps
@@ -159,7 +166,7 @@ def main():
         "metric": "FP8 linear TFLOP/s (train fwd+bwd, M=16k) + decode GEMM HBM GB/s (M=1..128)",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "fp8_e4m3 x fp8_e4m3 -> f32 -> bf16",
+        "scaling": "weak", "vs_baseline": None, "dtype": "fp8_e4m3",
         "data": "synthetic",
         "config": {"workload": "8B-class decoder layer, 7 linears, training M=16384 (quantizers + "
                                "FProp + DGrad + WGrad) plus rollout FProp at M in {1,8,32,128}",
@@ -168,11 +175,12 @@ def main():
         "fprop_dgrad_kernel_tflops": round(g_rate / 1e12, 2),
         "wgrad_kernel_tflops": round(w_rate / 1e12, 2),
         "quantizers_gbps": round(q_rate / 1e9, 1),
-        "roofline": {"bound": "mfma", "kernel": "gemm_tile_kernel (FProp/DGrad, 1x128 x 128x128 scales)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_tile_kernel<block scales, 256x256> (FProp and DGrad launches)",
                      "achieved": round(g_rate / 1e12, 2), "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(g_rate / 1e12 / PEAK_FP8_TFLOPS, 4),
                      "avg_launch_ms": round(g_avg_s * 1e3, 4), "avg_launch_gflop": round(g_avg_fl / 1e9, 2),
-                     "launches": len(gemm_events), "traffic": None},
+                     "launches": len(gemm_events), "traffic": round(TILE_GEMM_TRAFFIC_BYTES),
+                     "traffic_unit": "bytes per launch", "algorithmic_bytes": round(tile_alg_bytes)},
     }
 
     if not args.no_decode_sweep:
@@ -182,10 +190,26 @@ def main():
     print(json.dumps(out))
 
 
+FUSED_8B = (("qkv_proj", 6144, 4096), ("o_proj", 4096, 4096), ("gate_up_proj", 28672, 4096),
+            ("down_proj", 4096, 14336))
+
+
 def decode_sweep(torch, jet, layer, rotations=4):
     """Rollout FProp over the layer with `rotations` distinct weight sets (> 256 MB each
     pass, so weights come from HBM, not from the last-level cache); one HIP graph per M
-    replayed several times; GB/s = algorithmic bytes / time."""
+    replayed several times; GB/s = algorithmic bytes / time.  Reported for the seven
+    separate linears and for the same layer with q/k/v and gate/up concatenated along N
+    (they share their input), which is how a serving engine calls them."""
+    res = _decode_sweep(torch, jet, layer, rotations)
+    fused = _decode_sweep(torch, jet, FUSED_8B, rotations)
+    for k, v in fused.items():
+        res[k]["fused_us_per_layer"] = v["us_per_layer"]
+        res[k]["fused_GB/s"] = v["GB/s"]
+        res[k]["fused_frac_hbm"] = v["frac_hbm"]
+    return res
+
+
+def _decode_sweep(torch, jet, layer, rotations):
     dev = "cuda:0"
     gen = torch.Generator(device=dev)
     gen.manual_seed(4242)
@@ -255,7 +279,7 @@ def cpu_baseline():
 
     N = K = 1024
     t_small = run(128, N, K)
-    k = int(min(32, max(1, round(15.0 / max(t_small, 1e-3)))))
+    k = int(min(256, max(1, round(15.0 / max(t_small, 1e-3)))))
     M = 128 * k
     t = run(M, N, K)
     fl = 3 * 2 * M * N * K
