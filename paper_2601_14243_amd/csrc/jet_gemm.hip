@@ -397,13 +397,15 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
 constexpr int kSkWaves = 4;
 constexpr int kSkRun = 8;                                // consecutive groups per wave per pass
 constexpr int kSkPass = kSkWaves * kSkRun;               // groups chained per pass
-constexpr int kSkDepth = 6;                              // units in flight per wave
 constexpr int kSkUnitBytes = 2048 + 2048 + 256;          // weight fragment, activation fragment, scales
-constexpr int kSkRingBytes = kSkDepth * kSkUnitBytes;
 constexpr int kSkGroupBytes = 4 * 64 * 4 + 64 * 4;       // p[4][64] + s[64]
-constexpr int kSkLdsBytes = kSkWaves * kSkRingBytes + kSkPass * kSkGroupBytes;
+constexpr int sk_lds_bytes(int depth) { return kSkWaves * depth * kSkUnitBytes + kSkPass * kSkGroupBytes; }
 constexpr int kSkCopies = 5;                             // vector-memory operations per unit
 
+// kSkDepth = units in flight per wave: 6 when there is at most one workgroup per CU, 2 when the
+// strips outnumber the CUs (two workgroups then share a CU and cover each other's start-up,
+// chain passes and drain)
+template <int kSkDepth>
 __global__ __launch_bounds__(64 * kSkWaves) void gemm_skinny_kernel(const uint8_t* __restrict__ A,
                                                                      const float* __restrict__ sa,
                                                                      const uint8_t* __restrict__ B,
@@ -413,6 +415,7 @@ __global__ __launch_bounds__(64 * kSkWaves) void gemm_skinny_kernel(const uint8_
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_ptr_t)smem;
     const int t = threadIdx.x, w = t >> 6, l = t & 63, r = l & 15, c4 = l >> 4;
+    constexpr int kSkRingBytes = kSkDepth * kSkUnitBytes;
     const int G = R / kGroup;
     const int j0 = blockIdx.x * 16;
 
@@ -772,7 +775,8 @@ hipError_t launch_gemm(const uint8_t* A, const float* sa, const uint8_t* B, cons
         if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbRow, JET_BIG>, BigCfg::kLdsBytes);
         if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbBlock, JET_SMALL>, SmallCfg::kLdsBytes);
         if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbRow, JET_SMALL>, SmallCfg::kLdsBytes);
-        if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel, kSkLdsBytes);
+        if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<6>, sk_lds_bytes(6));
+        if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<2>, sk_lds_bytes(2));
         if (e == hipSuccess) e = allow_lds(gemm_strip_kernel<JET_STRIP_SMALL>, StripSmall::kLdsBytes);
         if (e == hipSuccess) e = allow_lds(gemm_strip_kernel<JET_STRIP_WIDE>, StripWide::kLdsBytes);
         attr_err = e;
@@ -781,8 +785,12 @@ hipError_t launch_gemm(const uint8_t* A, const float* sa, const uint8_t* B, cons
 
     uint16_t* o = static_cast<uint16_t*>(out);
     if (I <= 16 && sb_mode == kSbBlock) {
-        hipLaunchKernelGGL(gemm_skinny_kernel, dim3((unsigned)(J / 16)), dim3(64 * kSkWaves), kSkLdsBytes,
-                           st, A, sa, B, sb, o, (int)I, (int)J, (int)R);
+        if (J / 16 <= 256)
+            hipLaunchKernelGGL(gemm_skinny_kernel<6>, dim3((unsigned)(J / 16)), dim3(64 * kSkWaves),
+                               sk_lds_bytes(6), st, A, sa, B, sb, o, (int)I, (int)J, (int)R);
+        else
+            hipLaunchKernelGGL(gemm_skinny_kernel<2>, dim3((unsigned)(J / 16)), dim3(64 * kSkWaves),
+                               sk_lds_bytes(2), st, A, sa, B, sb, o, (int)I, (int)J, (int)R);
         return hipGetLastError();
     }
     if (I <= 256 && sb_mode == kSbBlock) {
