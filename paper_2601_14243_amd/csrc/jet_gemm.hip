@@ -36,6 +36,14 @@ __device__ __forceinline__ void dma16(uint32_t lds, const void* base, uint32_t v
                  : "s"(lds), "v"(voff), "s"(base)
                  : "memory");
 }
+// same, LDS address = lds_base + IMM formed directly in M0 (one scalar instruction)
+template <int IMM>
+__device__ __forceinline__ void dma16_at(uint32_t lds_base, const void* base, uint32_t voff) {
+    asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_base), "v"(voff), "s"(base), "n"(IMM)
+                 : "memory", "scc");
+}
 __device__ __forceinline__ void dma4(uint32_t lds, const float* ptr) {
     lds = __builtin_amdgcn_readfirstlane(lds);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off"
@@ -164,18 +172,21 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
     // Block c holds tile rows 32w + 8c .. + 7; lane l copies 16 bytes of row 32w + 8c + (l>>3):
     // chunk (l&7) ^ swizzle(row), swizzle = (row>>1)&7 = (l>>4) | ((c&1)<<2).
     struct Cursor {
-        const uint8_t *baseA, *baseB;   // tile origins (wave-uniform)
-        const float* gs;                // this lane's scale row
+        const uint8_t *pa, *pb;         // operand tiles of the step: tile origin + 128 g (wave-uniform)
+        const float* gs;                // this lane's scale of the step
         int k, g, rows;                 // tile in the list, group, valid A rows of the tile
     };
     const uint32_t lane_row = 32 * w + (l >> 3);
     const uint32_t lane_chunk = 16 * ((l & 7) ^ (l >> 4));
+    uint32_t offB[4];                   // B rows never run past the end: fixed per-lane offsets
+#pragma unroll
+    for (int i = 0; i < 4; ++i) offB[i] = (lane_row + 8 * i) * (uint32_t)R + (lane_chunk ^ ((i & 1) * 64));
     auto cursor_at_tile = [&](int k) {
         int i0, j0;
         tile_origin(k, i0, j0);
         Cursor c;
-        c.baseA = static_cast<const uint8_t*>(uniform_ptr(A + (size_t)i0 * R));
-        c.baseB = static_cast<const uint8_t*>(uniform_ptr(B + (size_t)j0 * R));
+        c.pa = static_cast<const uint8_t*>(uniform_ptr(A + (size_t)i0 * R));
+        c.pb = static_cast<const uint8_t*>(uniform_ptr(B + (size_t)j0 * R));
         c.k = k;
         c.g = 0;
         c.rows = I - i0;
@@ -192,27 +203,41 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
     // tiles are then copied again into a stage nobody reads: harmless, and branch-free)
     auto cursor_after = [&](const Cursor& c) {
         Cursor n = c;
-        if (c.g + 1 < G) n.g = c.g + 1;
-        else if (c.k + 1 < mine.count) n = cursor_at_tile(c.k + 1);
+        if (c.g + 1 < G) {
+            n.g = c.g + 1;
+            n.pa = c.pa + kGroup;
+            n.pb = c.pb + kGroup;
+            n.gs = c.gs + 1;
+        } else if (c.k + 1 < mine.count) {
+            n = cursor_at_tile(c.k + 1);
+        }
         return n;
     };
     const uint32_t ldsw = __builtin_amdgcn_readfirstlane(lds0 + 4 * w * 1024);
     const uint32_t ldss = __builtin_amdgcn_readfirstlane(lds0 + C::kABytes + C::kBBytes + w * 256);
     constexpr int kCopies = 9;
-    // copy i (0..8) of step c into stage `slot`: A blocks, B blocks, scale line
-    auto copy_one = [&](const Cursor& c, int i, int slot) {
-        const uint32_t st = slot * C::kStageBytes;
+    // copy i (0..8) of step c into the stage at LDS offset st: A blocks, B blocks, scale line
+    auto copy_one = [&](const Cursor& c, int i, uint32_t st) {
+        const uint32_t base = ldsw + st;
         if (i < 4) {
             // rows past the end of A repeat the last valid one (their outputs are never stored)
             const uint32_t row = min(lane_row + 8 * i, (uint32_t)(c.rows - 1));
-            const uint32_t off = row * (uint32_t)R + (lane_chunk ^ ((i & 1) * 64));
-            dma16(ldsw + st + i * 1024, c.baseA + (size_t)c.g * kGroup, off);
+            const uint32_t off = __umul24(row, (uint32_t)R) + (lane_chunk ^ ((i & 1) * 64));
+            switch (i) {
+                case 0: dma16_at<0>(base, c.pa, off); break;
+                case 1: dma16_at<1024>(base, c.pa, off); break;
+                case 2: dma16_at<2048>(base, c.pa, off); break;
+                default: dma16_at<3072>(base, c.pa, off); break;
+            }
         } else if (i < 8) {
-            const uint32_t off = lane_row * (uint32_t)R + (lane_chunk ^ ((i & 1) * 64));
-            dma16(ldsw + st + C::kABytes + (i - 4) * 1024,
-                  c.baseB + (size_t)c.g * kGroup + (size_t)(8 * (i - 4)) * R, off);
+            switch (i) {
+                case 4: dma16_at<C::kABytes>(base, c.pb, offB[0]); break;
+                case 5: dma16_at<C::kABytes + 1024>(base, c.pb, offB[1]); break;
+                case 6: dma16_at<C::kABytes + 2048>(base, c.pb, offB[2]); break;
+                default: dma16_at<C::kABytes + 3072>(base, c.pb, offB[3]); break;
+            }
         } else {
-            dma4(ldss + st, c.gs + c.g);
+            dma4(ldss + st, c.gs);
         }
     };
 
@@ -272,13 +297,13 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
     // ---- prologue: step 0 into stage 0, first copies of step 1, fragments of step 0 ----
     Cursor cur = cursor_at_tile(0);
 #pragma unroll
-    for (int i = 0; i < kCopies; ++i) copy_one(cur, i, 0);
+    for (int i = 0; i < kCopies; ++i) copy_one(cur, i, 0u);
     cur = cursor_after(cur);
     JET_WAIT_VMCNT(0);
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 #pragma unroll
-    for (int i = 0; i < kLate; ++i) copy_one(cur, i, 1);
+    for (int i = 0; i < kLate; ++i) copy_one(cur, i, (uint32_t)C::kStageBytes);
 
     v8i cf[TN], xf[2];
     RawScales next;
@@ -297,6 +322,8 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
     for (int q = 0, k = 0, g = 0; q < n_steps; ++q) {
         const int slot = q & 1;
         const Cursor after = cursor_after(cur);     // step q+2 (all control flow of a step is here)
+        const uint32_t st_this = __builtin_amdgcn_readfirstlane(slot * C::kStageBytes);
+        const uint32_t st_other = __builtin_amdgcn_readfirstlane((slot ^ 1) * C::kStageBytes);
 
         // ---- one straight-line block from here to the end of the tile loop ----
         // scales of this step: s = sa * sb, one binary32 product per (row, column scale)
@@ -345,10 +372,10 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (t > kSync) {
-                copy_one(cur, t - kSync - 1, slot);   // copies 0 .. kLate-1 of step q+2
+                copy_one(cur, t - kSync - 1, st_this);   // copies 0 .. kLate-1 of step q+2
                 __builtin_amdgcn_sched_barrier(0);
             } else if (t < kCopies - kLate) {
-                copy_one(cur, kLate + t, slot ^ 1);   // remaining copies of step q+1
+                copy_one(cur, kLate + t, st_other);   // remaining copies of step q+1
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
