@@ -421,18 +421,21 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
 // for the ring.  Every 32 groups the p_g and s_g meet in LDS and the four waves run
 // the ordered fma chain for their quarter of the outputs.
 // ------------------------------------------------------------------------
-constexpr int kSkWaves = 4;
-constexpr int kSkRun = 8;                                // consecutive groups per wave per pass
-constexpr int kSkPass = kSkWaves * kSkRun;               // groups chained per pass
+#ifndef JET_SK8_MIN_R
+#define JET_SK8_MIN_R 1024   /* reduction length from which 8 waves split a strip */
+#endif
+constexpr int kSkPass = 32;                              // groups chained per pass
 constexpr int kSkUnitBytes = 2048 + 2048 + 256;          // weight fragment, activation fragment, scales
 constexpr int kSkGroupBytes = 4 * 64 * 4 + 64 * 4;       // p[4][64] + s[64]
-constexpr int sk_lds_bytes(int depth) { return kSkWaves * depth * kSkUnitBytes + kSkPass * kSkGroupBytes; }
+constexpr int sk_lds_bytes(int depth, int waves) { return waves * depth * kSkUnitBytes + kSkPass * kSkGroupBytes; }
 constexpr int kSkCopies = 5;                             // vector-memory operations per unit
 
-// kSkDepth = units in flight per wave: 6 when there is at most one workgroup per CU, 2 when the
-// strips outnumber the CUs (two workgroups then share a CU and cover each other's start-up,
+// kSkDepth = units in flight per wave: 3 or 6 when there is at most one workgroup per CU, 1 when
+// the strips outnumber the CUs (two workgroups then share a CU and cover each other's start-up,
 // chain passes and drain)
-template <int kSkDepth>
+// kSkWaves = waves splitting the groups of a strip (runs of 32 / kSkWaves consecutive groups):
+// 8 for long reductions, where a wave's serial walk through its units is what limits the stream
+template <int kSkDepth, int kSkWaves>
 __global__ __launch_bounds__(64 * kSkWaves) void gemm_skinny_kernel(const uint8_t* __restrict__ A,
                                                                      const float* __restrict__ sa,
                                                                      const uint8_t* __restrict__ B,
@@ -443,6 +446,7 @@ __global__ __launch_bounds__(64 * kSkWaves) void gemm_skinny_kernel(const uint8_
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_ptr_t)smem;
     const int t = threadIdx.x, w = t >> 6, l = t & 63, r = l & 15, c4 = l >> 4;
     constexpr int kSkRingBytes = kSkDepth * kSkUnitBytes;
+    constexpr int kSkRun = kSkPass / kSkWaves;               // consecutive groups per wave per pass
     const int G = R / kGroup;
     const int j0 = blockIdx.x * 16;
 
@@ -514,13 +518,15 @@ __global__ __launch_bounds__(64 * kSkWaves) void gemm_skinny_kernel(const uint8_
             if (i + kSkDepth < n_units) issue(i + kSkDepth);
         }
         __syncthreads();
-        for (int g = 0; g < ng; ++g) {
-            const float* src = reinterpret_cast<const float*>(pass_p + g * kSkGroupBytes);
-            acc = chain(src[w * 64 + l], src[256 + l], acc);
+        if (w < 4) {                                     // waves 0-3 run the chain (wave-uniform)
+            for (int g = 0; g < ng; ++g) {
+                const float* src = reinterpret_cast<const float*>(pass_p + g * kSkGroupBytes);
+                acc = chain(src[w * 64 + l], src[256 + l], acc);
+            }
         }
         __syncthreads();
     }
-    if (r < I) out[(size_t)r * J + j0 + 4 * c4 + w] = (uint16_t)bf16_rne(acc);
+    if (w < 4 && r < I) out[(size_t)r * J + j0 + 4 * c4 + w] = (uint16_t)bf16_rne(acc);
 }
 
 // ------------------------------------------------------------------------
@@ -802,8 +808,9 @@ hipError_t launch_gemm(const uint8_t* A, const float* sa, const uint8_t* B, cons
         if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbRow, JET_BIG>, BigCfg::kLdsBytes);
         if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbBlock, JET_SMALL>, SmallCfg::kLdsBytes);
         if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbRow, JET_SMALL>, SmallCfg::kLdsBytes);
-        if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<6>, sk_lds_bytes(6));
-        if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<2>, sk_lds_bytes(2));
+        if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<6, 4>, sk_lds_bytes(6, 4));
+        if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<3, 8>, sk_lds_bytes(3, 8));
+        if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<1, 8>, sk_lds_bytes(1, 8));
         if (e == hipSuccess) e = allow_lds(gemm_strip_kernel<JET_STRIP_SMALL>, StripSmall::kLdsBytes);
         if (e == hipSuccess) e = allow_lds(gemm_strip_kernel<JET_STRIP_WIDE>, StripWide::kLdsBytes);
         attr_err = e;
@@ -812,12 +819,16 @@ hipError_t launch_gemm(const uint8_t* A, const float* sa, const uint8_t* B, cons
 
     uint16_t* o = static_cast<uint16_t*>(out);
     if (I <= 16 && sb_mode == kSbBlock) {
-        if (J / 16 <= 256)
-            hipLaunchKernelGGL(gemm_skinny_kernel<6>, dim3((unsigned)(J / 16)), dim3(64 * kSkWaves),
-                               sk_lds_bytes(6), st, A, sa, B, sb, o, (int)I, (int)J, (int)R);
+        const unsigned strips = (unsigned)(J / 16);
+        if (strips > 256)   // two workgroups (16 waves) per CU, one unit in flight per wave
+            hipLaunchKernelGGL((gemm_skinny_kernel<1, 8>), dim3(strips), dim3(512), sk_lds_bytes(1, 8), st, A, sa,
+                               B, sb, o, (int)I, (int)J, (int)R);
+        else if (R >= JET_SK8_MIN_R)
+            hipLaunchKernelGGL((gemm_skinny_kernel<3, 8>), dim3(strips), dim3(512), sk_lds_bytes(3, 8), st, A, sa,
+                               B, sb, o, (int)I, (int)J, (int)R);
         else
-            hipLaunchKernelGGL(gemm_skinny_kernel<2>, dim3((unsigned)(J / 16)), dim3(64 * kSkWaves),
-                               sk_lds_bytes(2), st, A, sa, B, sb, o, (int)I, (int)J, (int)R);
+            hipLaunchKernelGGL((gemm_skinny_kernel<6, 4>), dim3(strips), dim3(256), sk_lds_bytes(6, 4), st, A, sa,
+                               B, sb, o, (int)I, (int)J, (int)R);
         return hipGetLastError();
     }
     if (I <= 256 && sb_mode == kSbBlock) {
