@@ -415,27 +415,27 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
 // Skinny kernel for I <= 16 (decode): bound by streaming B (the weights) once.
 // A workgroup of 4 waves owns 16 output columns and the whole reduction.  The
 // groups are dealt to the waves in runs of 8; every wave streams its own units
-// (16 weight rows + the 16 activation rows + scales of one group, 4.25 KB) through
+// (16 weight rows + the 16 or 32 activation rows + scales of one group) through
 // a private LDS ring with kSkDepth units in flight, using the same whole-line
 // LDS-DMA and swizzled fragment layout as the tile kernel -- no barrier is needed
-// for the ring.  Every 32 groups the p_g and s_g meet in LDS and the four waves run
-// the ordered fma chain for their quarter of the outputs.
+// for the ring.  Every 32 (16) groups the p_g and s_g meet in LDS and four waves per row
+// tile run the ordered fma chain for their quarter of the outputs.
 // ------------------------------------------------------------------------
-#ifndef JET_SK8_MIN_R
-#define JET_SK8_MIN_R 1024   /* reduction length from which 8 waves split a strip */
-#endif
-constexpr int kSkPass = 32;                              // groups chained per pass
-constexpr int kSkUnitBytes = 2048 + 2048 + 256;          // weight fragment, activation fragment, scales
-constexpr int kSkGroupBytes = 4 * 64 * 4 + 64 * 4;       // p[4][64] + s[64]
-constexpr int sk_lds_bytes(int depth, int waves) { return waves * depth * kSkUnitBytes + kSkPass * kSkGroupBytes; }
-constexpr int kSkCopies = 5;                             // vector-memory operations per unit
+constexpr int sk_unit_bytes(int rm) { return 2048 + rm * 2048 + 256; }    // weight fragment, RM activation fragments, scales
+constexpr int sk_group_bytes(int rm) { return rm * (4 * 64 * 4 + 64 * 4); } // per row tile: p[4][64] + s[64]
+constexpr int sk_pass(int rm) { return 32 / rm; }                          // groups chained per pass
+constexpr int sk_lds_bytes(int depth, int waves, int rm) {
+    return waves * depth * sk_unit_bytes(rm) + sk_pass(rm) * sk_group_bytes(rm);
+}
 
 // kSkDepth = units in flight per wave: 3 or 6 when there is at most one workgroup per CU, 1 when
 // the strips outnumber the CUs (two workgroups then share a CU and cover each other's start-up,
 // chain passes and drain)
-// kSkWaves = waves splitting the groups of a strip (runs of 32 / kSkWaves consecutive groups):
-// 8 for long reductions, where a wave's serial walk through its units is what limits the stream
-template <int kSkDepth, int kSkWaves>
+// kSkWaves = waves splitting the groups of a strip (runs of consecutive groups): 8 unless the
+// reduction is very short
+// RM = 16-row tiles of the batch (1: I <= 16, 2: I <= 32); a unit then carries RM activation
+// fragments and gives RM MFMAs with the same weight fragment
+template <int kSkDepth, int kSkWaves, int RM>
 __global__ __launch_bounds__(64 * kSkWaves) void gemm_skinny_kernel(const uint8_t* __restrict__ A,
                                                                      const float* __restrict__ sa,
                                                                      const uint8_t* __restrict__ B,
@@ -445,23 +445,29 @@ __global__ __launch_bounds__(64 * kSkWaves) void gemm_skinny_kernel(const uint8_
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_ptr_t)smem;
     const int t = threadIdx.x, w = t >> 6, l = t & 63, r = l & 15, c4 = l >> 4;
-    constexpr int kSkRingBytes = kSkDepth * kSkUnitBytes;
-    constexpr int kSkRun = kSkPass / kSkWaves;               // consecutive groups per wave per pass
+    constexpr int kUnit = sk_unit_bytes(RM), kGroupBytes = sk_group_bytes(RM), kPass = sk_pass(RM);
+    constexpr int kSkRingBytes = kSkDepth * kUnit;
+    constexpr int kSkRun = kPass / kSkWaves;                 // consecutive groups per wave per pass
+    constexpr int kCopies = 2 + 2 * RM + 1;                  // vector-memory operations per unit
+    static_assert(kSkRun >= 1 && RM <= 2 && 4 * RM <= kSkWaves && (kSkDepth - 1) * kCopies < 64, "");
     const int G = R / kGroup;
     const int j0 = blockIdx.x * 16;
 
-    // copy offsets of this lane: block b = rows 8b..8b+7 of a fragment, one line per 8 lanes
-    uint32_t offW[2], offX[2];
+    // copy offsets of this lane: block b = rows 8b..8b+7, one line per 8 lanes
+    uint32_t offW[2], offX[2 * RM];
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
         const int row = 8 * b + (l >> 3);
-        const int chunk = (l & 7) ^ ((row >> 1) & 7);
-        offW[b] = (uint32_t)row * (uint32_t)R + 16 * chunk;
-        offX[b] = (uint32_t)min(row, I - 1) * (uint32_t)R + 16 * chunk;
+        offW[b] = (uint32_t)row * (uint32_t)R + 16 * ((l & 7) ^ ((row >> 1) & 7));
+    }
+#pragma unroll
+    for (int b = 0; b < 2 * RM; ++b) {
+        const int row = 8 * b + (l >> 3);
+        offX[b] = (uint32_t)min(row, I - 1) * (uint32_t)R + 16 * ((l & 7) ^ ((row >> 1) & 7));
     }
     const uint8_t* baseW = B + (size_t)j0 * R;
-    // scale line of a unit: lanes 0-15 fetch sa of rows 0-15 (clamped), the rest the block scale
-    const float* gs = (l < 16) ? sa + (size_t)min(l, I - 1) * G : sb + (size_t)(j0 >> 7) * G;
+    // scale line of a unit: lanes 0 .. 16 RM - 1 fetch sa of the batch rows (clamped), lanes 32-63 the block scale
+    const float* gs = (l < 32) ? sa + (size_t)min(l, I - 1) * G : sb + (size_t)(j0 >> 7) * G;
     const int swz = (r >> 1) & 7;
     const int frag_lo = (r >> 3) * 1024 + (r & 7) * 128 + 16 * (c4 ^ swz);
     const int frag_hi = (r >> 3) * 1024 + (r & 7) * 128 + 16 * ((4 + c4) ^ swz);
@@ -471,62 +477,68 @@ __global__ __launch_bounds__(64 * kSkWaves) void gemm_skinny_kernel(const uint8_
     uint8_t* const pass_p = smem + kSkWaves * kSkRingBytes;
 
     // unit i of this wave is group seq(i); the wave has n_units of them
-    auto seq = [&](int i) { return (i / kSkRun) * kSkPass + w * kSkRun + (i % kSkRun); };
-    const int full = G / kSkPass, tail = G - full * kSkPass;
+    auto seq = [&](int i) { return (i / kSkRun) * kPass + w * kSkRun + (i % kSkRun); };
+    const int full = G / kPass, tail = G - full * kPass;
     const int n_units = full * kSkRun + max(0, min(kSkRun, tail - w * kSkRun));
 
     auto issue = [&](int i) {
         const int g = seq(i);
-        const uint32_t u = ring + (i % kSkDepth) * kSkUnitBytes;
+        const uint32_t u = ring + (i % kSkDepth) * kUnit;
         dma16(u, baseW + (size_t)g * kGroup, offW[0]);
         dma16(u + 1024, baseW + (size_t)g * kGroup, offW[1]);
-        dma16(u + 2048, A + (size_t)g * kGroup, offX[0]);
-        dma16(u + 3072, A + (size_t)g * kGroup, offX[1]);
-        dma4(u + 4096, gs + g);
+#pragma unroll
+        for (int b = 0; b < 2 * RM; ++b) dma16(u + 2048 + b * 1024, A + (size_t)g * kGroup, offX[b]);
+        dma4(u + 2048 + RM * 2048, gs + g);
     };
 
     for (int i = 0; i < kSkDepth && i < n_units; ++i) issue(i);
 
-    float acc = 0.0f;  // output (row r, column j0 + 4 c4 + w)
+    // chain owner: wave w < 4 RM owns row tile w >> 2 and the columns j0 + 4 c4 + (w & 3)
+    const int cm = w >> 2, cq = w & 3;
+    float acc = 0.0f;
     int i = 0;
-    for (int g0 = 0; g0 < G; g0 += kSkPass) {
-        const int ng = min(kSkPass, G - g0);
+    for (int g0 = 0; g0 < G; g0 += kPass) {
+        const int ng = min(kPass, G - g0);
         for (int j = 0; j < kSkRun; ++j, ++i) {
             if (i >= n_units) break;                 // wave-uniform
             // unit i has landed once at most the younger units' copies are outstanding
             const int younger = min(n_units, i + kSkDepth) - i - 1;
             switch (younger) {
                 case 0: JET_WAIT_VMCNT(0); break;
-                case 1: JET_WAIT_VMCNT(kSkCopies); break;
-                case 2: JET_WAIT_VMCNT(2 * kSkCopies); break;
-                case 3: JET_WAIT_VMCNT(3 * kSkCopies); break;
-                case 4: JET_WAIT_VMCNT(4 * kSkCopies); break;
-                default: JET_WAIT_VMCNT(5 * kSkCopies); break;
+                case 1: JET_WAIT_VMCNT(kCopies); break;
+                case 2: JET_WAIT_VMCNT(2 * kCopies); break;
+                case 3: JET_WAIT_VMCNT(3 * kCopies); break;
+                case 4: JET_WAIT_VMCNT(4 * kCopies); break;
+                default: JET_WAIT_VMCNT(5 * kCopies); break;
             }
             asm volatile("" ::: "memory");
-            const uint8_t* u = ring_p + (i % kSkDepth) * kSkUnitBytes;
+            const uint8_t* u = ring_p + (i % kSkDepth) * kUnit;
             const v8i wf = load_frag(u + frag_lo, u + frag_hi);
-            const v8i xf = load_frag(u + 2048 + frag_lo, u + 2048 + frag_hi);
-            const float s = *reinterpret_cast<const float*>(u + 4096 + 4 * r) *
-                            *reinterpret_cast<const float*>(u + 4096 + 64);
-            const v4f p = group_product(wf, xf);
-            float* dst = reinterpret_cast<float*>(pass_p + (seq(i) - g0) * kSkGroupBytes);
+            const float sbv = *reinterpret_cast<const float*>(u + 2048 + RM * 2048 + 128);
+            float* dst = reinterpret_cast<float*>(pass_p + (seq(i) - g0) * kGroupBytes);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) dst[e * 64 + l] = p[e];
-            dst[256 + l] = s;
+            for (int m = 0; m < RM; ++m) {
+                const v8i xf = load_frag(u + 2048 + m * 2048 + frag_lo, u + 2048 + m * 2048 + frag_hi);
+                const float s = *reinterpret_cast<const float*>(u + 2048 + RM * 2048 + 4 * (16 * m + r)) * sbv;
+                const v4f p = group_product(wf, xf);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) dst[m * 320 + e * 64 + l] = p[e];
+                dst[m * 320 + 256 + l] = s;
+            }
             asm volatile("" ::: "memory");
             if (i + kSkDepth < n_units) issue(i + kSkDepth);
         }
         __syncthreads();
-        if (w < 4) {                                     // waves 0-3 run the chain (wave-uniform)
+        if (w < 4 * RM) {                                // wave-uniform
             for (int g = 0; g < ng; ++g) {
-                const float* src = reinterpret_cast<const float*>(pass_p + g * kSkGroupBytes);
-                acc = chain(src[w * 64 + l], src[256 + l], acc);
+                const float* src = reinterpret_cast<const float*>(pass_p + g * kGroupBytes) + cm * 320;
+                acc = chain(src[cq * 64 + l], src[256 + l], acc);
             }
         }
         __syncthreads();
     }
-    if (w < 4 && r < I) out[(size_t)r * J + j0 + 4 * c4 + w] = (uint16_t)bf16_rne(acc);
+    const int row = 16 * cm + r;
+    if (w < 4 * RM && row < I) out[(size_t)row * J + j0 + 4 * c4 + cq] = (uint16_t)bf16_rne(acc);
 }
 
 // ------------------------------------------------------------------------
@@ -808,9 +820,10 @@ hipError_t launch_gemm(const uint8_t* A, const float* sa, const uint8_t* B, cons
         if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbRow, JET_BIG>, BigCfg::kLdsBytes);
         if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbBlock, JET_SMALL>, SmallCfg::kLdsBytes);
         if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbRow, JET_SMALL>, SmallCfg::kLdsBytes);
-        if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<6, 4>, sk_lds_bytes(6, 4));
-        if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<3, 8>, sk_lds_bytes(3, 8));
-        if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<1, 8>, sk_lds_bytes(1, 8));
+        if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<6, 4, 1>, sk_lds_bytes(6, 4, 1));
+        if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<3, 8, 1>, sk_lds_bytes(3, 8, 1));
+        if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<1, 8, 1>, sk_lds_bytes(1, 8, 1));
+        if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<2, 8, 2>, sk_lds_bytes(2, 8, 2));
         if (e == hipSuccess) e = allow_lds(gemm_strip_kernel<JET_STRIP_SMALL>, StripSmall::kLdsBytes);
         if (e == hipSuccess) e = allow_lds(gemm_strip_kernel<JET_STRIP_WIDE>, StripWide::kLdsBytes);
         attr_err = e;
@@ -818,17 +831,23 @@ hipError_t launch_gemm(const uint8_t* A, const float* sa, const uint8_t* B, cons
     if (attr_err != hipSuccess) return attr_err;
 
     uint16_t* o = static_cast<uint16_t*>(out);
-    if (I <= 16 && sb_mode == kSbBlock) {
+    // decode: a workgroup per 16-column strip; shape-only choice of ring depth / wave count
+    // (17-32 rows with more strips than CUs go to the strip kernel below: measured faster)
+    if ((I <= 16 || (I <= 32 && J / 16 <= 256)) && sb_mode == kSbBlock) {
         const unsigned strips = (unsigned)(J / 16);
-        if (strips > 256)   // two workgroups (16 waves) per CU, one unit in flight per wave
-            hipLaunchKernelGGL((gemm_skinny_kernel<1, 8>), dim3(strips), dim3(512), sk_lds_bytes(1, 8), st, A, sa,
-                               B, sb, o, (int)I, (int)J, (int)R);
-        else if (R >= JET_SK8_MIN_R)
-            hipLaunchKernelGGL((gemm_skinny_kernel<3, 8>), dim3(strips), dim3(512), sk_lds_bytes(3, 8), st, A, sa,
-                               B, sb, o, (int)I, (int)J, (int)R);
-        else
-            hipLaunchKernelGGL((gemm_skinny_kernel<6, 4>), dim3(strips), dim3(256), sk_lds_bytes(6, 4), st, A, sa,
-                               B, sb, o, (int)I, (int)J, (int)R);
+#define JET_SKINNY(D, W, RMT)                                                                              \
+    hipLaunchKernelGGL((gemm_skinny_kernel<D, W, RMT>), dim3(strips), dim3(64 * W), sk_lds_bytes(D, W, RMT), \
+                       st, A, sa, B, sb, o, (int)I, (int)J, (int)R)
+        if (I > 16) {
+            JET_SKINNY(2, 8, 2);
+        } else if (strips > 256) {
+            JET_SKINNY(1, 8, 1);                        // two workgroups (16 waves) per CU
+        } else if (R >= 1024) {
+            JET_SKINNY(3, 8, 1);
+        } else {
+            JET_SKINNY(6, 4, 1);
+        }
+#undef JET_SKINNY
         return hipGetLastError();
     }
     if (I <= 256 && sb_mode == kSbBlock) {
