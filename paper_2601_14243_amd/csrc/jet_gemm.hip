@@ -551,7 +551,8 @@ __global__ __launch_bounds__(64 * kSkWaves) void gemm_skinny_kernel(const uint8_
 // shallower one for the activations.  The outstanding-copy counter of a wave retires in
 // issue order, so a wave that issued both streams could never keep the weights further
 // ahead than the activations: waves 0 and 1 copy only weights, waves 2 and 3 only
-// activations and scales.  One barrier per pair; the fragments of pair p+2 are fetched from
+// activations and scales (four dedicated copy waves next to the four computing ones, so that
+// no MFMA stream ever waits behind a copy).  One barrier per pair; the fragments of pair p+2 are fetched from
 // LDS into registers while pair p is computed, so neither the LDS latency nor the barrier
 // is paid per group.  Wave w owns RM*CN/4 of the MFMA tiles and runs their ordered fma
 // chains in registers: the same chain as every other kernel, so rows are bit-identical.
@@ -578,7 +579,7 @@ struct StripCfg {
 };
 
 template <int RM, int CN, int WDEPTH, int ADEPTH>
-__global__ __launch_bounds__(256) void gemm_strip_kernel(const uint8_t* __restrict__ A,
+__global__ __launch_bounds__(512) void gemm_strip_kernel(const uint8_t* __restrict__ A,
                                                           const float* __restrict__ sa,
                                                           const uint8_t* __restrict__ B,
                                                           const float* __restrict__ sb,
@@ -605,7 +606,9 @@ __global__ __launch_bounds__(256) void gemm_strip_kernel(const uint8_t* __restri
 
     // ---- copies: a wave copies kMine consecutive 1 KB blocks (8 rows) of each group of a
     // pair; block b is half b & 1 of fragment b >> 1 ----
-    const bool w_stream = w < 2;
+    // waves 0-3 compute (one per SIMD); waves 4-7 only copy: 4, 5 the weights, 6, 7 the activations
+    const bool copier = w >= 4;
+    const bool w_stream = w < 6;
     const int side = w & 1;
     constexpr int kWMine = CN, kAMine = RM;
     constexpr int kMineMax = RM > CN ? RM : CN;
@@ -624,8 +627,8 @@ __global__ __launch_bounds__(256) void gemm_strip_kernel(const uint8_t* __restri
             off[i] = (uint32_t)row * (uint32_t)R + (lane_chunk ^ ((blk & 1) * 64));
         }
     }
-    // scale line: wave 2 copies sa of the tile's rows (up to 64), wave 3 the block scale
-    const float* gs = (w == 2) ? sa + (size_t)min(i0 + l, I - 1) * G : sb + (size_t)(j0 >> 7) * G;
+    // scale line: wave 6 copies sa of the tile's rows (up to 64), wave 7 the block scale
+    const float* gs = (w == 6) ? sa + (size_t)min(i0 + l, I - 1) * G : sb + (size_t)(j0 >> 7) * G;
     const uint32_t lds_w = __builtin_amdgcn_readfirstlane(lds0 + side * kWMine * 1024);
     const uint32_t lds_a = __builtin_amdgcn_readfirstlane(lds0 + C::kWDepth * C::kWStage + side * kAMine * 1024);
     const uint32_t lds_s = __builtin_amdgcn_readfirstlane(lds0 + C::kWDepth * C::kWStage + RM * 2048 + side * 512);
@@ -648,7 +651,7 @@ __global__ __launch_bounds__(256) void gemm_strip_kernel(const uint8_t* __restri
     };
 
     // ---- this wave's MFMA tiles: rows m0 .. m0+kNM-1, columns n0 .. n0+kNN-1 (in tiles) ----
-    const int first = w * C::kTiles, m0 = first / CN, n0 = first % CN;
+    const int first = (w & 3) * C::kTiles, m0 = first / CN, n0 = first % CN;
     const int swz = (r >> 1) & 7;
     const int frag_lo = (r >> 3) * 1024 + (r & 7) * 128 + 16 * (c4 ^ swz);
     const int frag_hi = (r >> 3) * 1024 + (r & 7) * 128 + 16 * ((4 + c4) ^ swz);
@@ -716,7 +719,7 @@ __global__ __launch_bounds__(256) void gemm_strip_kernel(const uint8_t* __restri
         const int rows = min(C::BM, I - i0);
         const long lines = (long)rows * G;
         const uint32_t sink = __builtin_amdgcn_readfirstlane(lds0 + C::kWDepth * C::kWStage + C::kADepth * C::kAStage);
-        for (long x = (long)me * 256 + t; x < lines; x += (long)per_xcd * 256) {
+        for (long x = (long)me * 512 + t; x < lines; x += (long)per_xcd * 512) {
             const long row = x / G, g = x - row * G;
             dma4(sink, reinterpret_cast<const float*>(baseA + (size_t)row * R + (size_t)g * kGroup));
         }
@@ -726,20 +729,28 @@ __global__ __launch_bounds__(256) void gemm_strip_kernel(const uint8_t* __restri
     // iteration p of the main loop issues pair p + depth; the prologue issues pairs 0 .. depth-1
     // in the same relative order, so the steady-state counts hold from the start
     for (int v = 0; v < C::kWDepth; ++v)
-        if (w_stream || v < C::kADepth) issue(v);
-    wait_copies(C::kWDepth - 2);                     // pairs 0 and 1 landed: depth-2 later pairs outstanding
+        if (copier && (w_stream || v < C::kADepth)) issue(v);
+    if (copier) wait_copies(C::kWDepth - 2);         // pairs 0 and 1 landed: depth-2 later pairs outstanding
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    Operands op[3];
-    fetch(0, op[0]);
-    fetch(min(1, P - 1), op[1]);
-
-    // iteration p: pairs <= p+2 have landed; slot of pair p is free (its fragments are in registers)
+    // iteration p (one barrier): pairs <= p+2 have landed; the slots of pair p are free (its
+    // fragments are in registers).  The two kinds of wave run the same number of barriers.
+    if (copier) {
+        for (int p = 0; p < P; ++p) {
+            wait_copies(C::kWDepth - 3);
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            issue(p + (w_stream ? C::kWDepth : C::kADepth));
+        }
+        JET_WAIT_VMCNT(0);   // nothing may be in flight towards the LDS when it is released
+        return;
+    }
+    Operands op0, op1, op2;
+    fetch(0, op0);
+    fetch(min(1, P - 1), op1);
     auto iteration = [&](int p, const Operands& cur, Operands& nxt2) {
-        wait_copies(C::kWDepth - 3);
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        issue(p + (w_stream ? C::kWDepth : C::kADepth));
         fetch(min(p + 2, P - 1), nxt2);
         compute(p, cur);
         // my reads of pair p+1's slots are done before the next barrier lets them be overwritten
@@ -748,12 +759,12 @@ __global__ __launch_bounds__(256) void gemm_strip_kernel(const uint8_t* __restri
     };
     int p = 0;
     for (; p + 2 < P; p += 3) {
-        iteration(p, op[0], op[2]);
-        iteration(p + 1, op[1], op[0]);
-        iteration(p + 2, op[2], op[1]);
+        iteration(p, op0, op2);
+        iteration(p + 1, op1, op0);
+        iteration(p + 2, op2, op1);
     }
-    if (p < P) iteration(p, op[0], op[2]);
-    if (p + 1 < P) iteration(p + 1, op[1], op[0]);
+    if (p < P) iteration(p, op0, op2);
+    if (p + 1 < P) iteration(p + 1, op1, op0);
     JET_WAIT_VMCNT(0);   // nothing may be in flight towards the LDS when it is released
 
 #pragma unroll
@@ -853,11 +864,11 @@ hipError_t launch_gemm(const uint8_t* A, const float* sa, const uint8_t* B, cons
     if (I <= 256 && sb_mode == kSbBlock) {
         // decode batches: 32- or 64-row blocks x 32-column strips
         if (I <= 32) {
-            hipLaunchKernelGGL((gemm_strip_kernel<JET_STRIP_SMALL>), dim3((unsigned)(J / 32)), dim3(256),
+            hipLaunchKernelGGL((gemm_strip_kernel<JET_STRIP_SMALL>), dim3((unsigned)(J / 32)), dim3(512),
                                StripSmall::kLdsBytes, st, A, sa, B, sb, o, (int)I, (int)J, (int)R, 1);
         } else {
             const int rbs = (int)((I + 63) / 64);
-            hipLaunchKernelGGL((gemm_strip_kernel<JET_STRIP_WIDE>), dim3((unsigned)(rbs * (J / 32))), dim3(256),
+            hipLaunchKernelGGL((gemm_strip_kernel<JET_STRIP_WIDE>), dim3((unsigned)(rbs * (J / 32))), dim3(512),
                                StripWide::kLdsBytes, st, A, sa, B, sb, o, (int)I, (int)J, (int)R, rbs);
         }
         return hipGetLastError();
