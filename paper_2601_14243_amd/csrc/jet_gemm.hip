@@ -562,12 +562,12 @@ struct StripCfg {
     static constexpr int kWaves = 4;
     static constexpr int BM = 16 * RM, BN = 16 * CN;
     static constexpr int kWDepth = WDEPTH, kADepth = ADEPTH;    // ring depths in pairs
-    static constexpr int kWGroup = CN * 2048;                   // weight fragments of a group
-    static constexpr int kAGroup = RM * 2048 + 1024;            // activation fragments, sa[64] at +0, sb at +512
+    static constexpr int kWGroup = CN * 2048 + 512;             // weight fragments, then sa[64] and the sb line
+    static constexpr int kAGroup = RM * 2048;                   // activation fragments
     static constexpr int kWStage = 2 * kWGroup, kAStage = 2 * kAGroup;
     static constexpr int kSinkBytes = 256;                      // landing zone of the L2 warm-up loads
     static constexpr int kLdsBytes = kWDepth * kWStage + kADepth * kAStage + kSinkBytes;
-    static constexpr int kWOps = 2 * CN, kAOps = 2 * (RM + 1);  // copies per wave per pair
+    static constexpr int kWOps = 2 * (CN + 1), kAOps = 2 * RM;  // copies per wave per pair
     static constexpr int kTiles = RM * CN / kWaves;             // MFMA tiles per wave
     static constexpr int kNM = (kTiles + CN - 1) / CN;          // distinct row tiles per wave
     static constexpr int kNN = kTiles < CN ? kTiles : CN;       // distinct column tiles per wave
@@ -627,11 +627,12 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const uint8_t* __restri
             off[i] = (uint32_t)row * (uint32_t)R + (lane_chunk ^ ((blk & 1) * 64));
         }
     }
-    // scale line: wave 6 copies sa of the tile's rows (up to 64), wave 7 the block scale
-    const float* gs = (w == 6) ? sa + (size_t)min(i0 + l, I - 1) * G : sb + (size_t)(j0 >> 7) * G;
+    // scale lines travel with the weights (the weight waves have far fewer copies to issue than
+    // the activation waves): wave 4 copies sa of the tile's rows (up to 64), wave 5 the block scale
+    const float* gs = (w == 4) ? sa + (size_t)min(i0 + l, I - 1) * G : sb + (size_t)(j0 >> 7) * G;
     const uint32_t lds_w = __builtin_amdgcn_readfirstlane(lds0 + side * kWMine * 1024);
     const uint32_t lds_a = __builtin_amdgcn_readfirstlane(lds0 + C::kWDepth * C::kWStage + side * kAMine * 1024);
-    const uint32_t lds_s = __builtin_amdgcn_readfirstlane(lds0 + C::kWDepth * C::kWStage + RM * 2048 + side * 512);
+    const uint32_t lds_s = __builtin_amdgcn_readfirstlane(lds0 + CN * 2048 + side * 256);
     // this wave's copies of pair p (groups past the end repeat the last one)
     auto issue = [&](int p) {
 #pragma unroll
@@ -641,11 +642,11 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const uint8_t* __restri
                 const uint32_t st = (p % C::kWDepth) * C::kWStage + h * C::kWGroup;
 #pragma unroll
                 for (int i = 0; i < kWMine; ++i) dma16(lds_w + st + i * 1024, baseW + (size_t)g * kGroup, off[i]);
+                dma4(lds_s + st, gs + g);
             } else {
                 const uint32_t st = (p % C::kADepth) * C::kAStage + h * C::kAGroup;
 #pragma unroll
                 for (int i = 0; i < kAMine; ++i) dma16(lds_a + st + i * 1024, baseA + (size_t)g * kGroup, off[i]);
-                dma4(lds_s + st, gs + g);
             }
         }
     };
@@ -670,9 +671,9 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const uint8_t* __restri
 #pragma unroll
             for (int m = 0; m < C::kNM; ++m) {
                 o.xf[h][m] = load_frag(pa + (m0 + m) * 2048 + frag_lo, pa + (m0 + m) * 2048 + frag_hi);
-                o.sa[h][m] = *reinterpret_cast<const float*>(pa + RM * 2048 + ((m0 + m) * 16 + r) * 4);
+                o.sa[h][m] = *reinterpret_cast<const float*>(pw + CN * 2048 + ((m0 + m) * 16 + r) * 4);
             }
-            o.sb[h] = *reinterpret_cast<const float*>(pa + RM * 2048 + 512);
+            o.sb[h] = *reinterpret_cast<const float*>(pw + CN * 2048 + 256);
         }
     };
     v4f acc[C::kNM][C::kNN];
