@@ -22,7 +22,7 @@
  *   - Errors are return codes only.  All argument checks happen on the host
  *     before anything is launched; on error nothing is written.
  *   - Sizes: every dimension at most 2^30; the reduction length of a GEMM (K for
- *     FProp, N for DGrad, M for WGrad) at most 2^24.  Larger: JET_ERR_SHAPE.
+ *     FProp, N for DGrad, M for WGrad) below 2^24.  Otherwise: JET_ERR_SHAPE.
  *   - Inputs must be finite (NaN / Inf: no fault, result unspecified).
  *   - Same inputs give the same bytes on every call; kernel selection depends
  *     on shapes only and does not change any output bit.

@@ -14,8 +14,8 @@ jet_status gemm_entry(const uint8_t* a, const float* sa, const uint8_t* b, const
     if (!a || !sa || !b || !sb || !out) return JET_ERR_NULL;
     if (I < 1 || J < 1 || R < 1) return JET_ERR_SHAPE;
     if (J % 128 || R % 128 || (i_mult_128 && I % 128)) return JET_ERR_SHAPE;
-    /* kernels form 32-bit byte offsets (row in tile) x R: reduction length at most 2^24 */
-    if (I > INT32_MAX / 2 || J > INT32_MAX / 2 || R > (1 << 24)) return JET_ERR_SHAPE;
+    /* kernels form 32-bit byte offsets (row in tile) x R with a 24-bit multiply: reduction length below 2^24 */
+    if (I > INT32_MAX / 2 || J > INT32_MAX / 2 || R >= (1 << 24)) return JET_ERR_SHAPE;
     if (misaligned(a) || misaligned(sa) || misaligned(b) || misaligned(sb) || misaligned(out))
         return JET_ERR_ALIGN;
     return after_launch(jet::launch_gemm(a, sa, b, sb, sb_mode, out, I, J, R, static_cast<hipStream_t>(stream)));
