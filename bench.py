@@ -183,11 +183,43 @@ def main():
                      "traffic_unit": "bytes per launch", "algorithmic_bytes": round(tile_alg_bytes)},
     }
 
+    out["roofline"].update(sustained_mfma(torch, jet, g_rate))
     if not args.no_decode_sweep:
         out["decode"] = decode_sweep(torch, jet, layer)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))
+
+
+def sustained_mfma(torch, jet, achieved_flops):
+    """Context for `frac`: the rate the same FP8 matrix-core instruction sustains on this machine
+    from registers alone (no LDS, no memory), with pseudo-random and with all-zero operands,
+    and the shader clock rocm-smi shows meanwhile.  Operand values change the power the
+    matrix cores draw and with it the clock; the published peak is at the full 2.4 GHz."""
+    import re
+    import subprocess
+    import threading
+
+    def sclk():
+        try:
+            o = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=20).stdout
+            m = re.search(r"sclk clock level:[^(]*\((\d+)Mhz\)", o)
+            return int(m.group(1)) if m else None
+        except Exception:
+            return None
+
+    res = {}
+    for name, zero in (("random", False), ("zero", True)):
+        clk = []
+        th = threading.Thread(target=lambda: clk.append(sclk()))
+        jet.probe_mfma_rate(workgroups=1024, iters=4000, zero_data=zero, repeats=3)    # bring the clock to its steady state
+        th.start()
+        r = jet.probe_mfma_rate(workgroups=1024, iters=4000, zero_data=zero, repeats=40)
+        th.join()
+        res[f"mfma_only_{name}_operands_tflops"] = round(r / 1e12, 1)
+        res[f"mfma_only_{name}_operands_sclk_mhz"] = clk[0] if clk else None
+    res["frac_of_mfma_only_random_operands"] = round(achieved_flops / 1e12 / res["mfma_only_random_operands_tflops"], 4)
+    return res
 
 
 FUSED_8B = (("qkv_proj", 6144, 4096), ("o_proj", 4096, 4096), ("gate_up_proj", 28672, 4096),

@@ -125,6 +125,19 @@ jet_status jet_fp8_linear_wgrad(const uint8_t* qdyT, const float* sdyT,
                                 void* dw, int64_t M, int64_t N, int64_t K,
                                 void* stream);
 
+/*
+ * Measurement aid for benchmarks; not a step of the layer.  Launches
+ * `workgroups` workgroups of 8 waves that each issue 32 * iters FP8 16x16x128
+ * matrix-core instructions on register operands (pseudo-random finite E4M3
+ * bytes, or all zero if zero_data != 0) and nothing else, so that a caller can
+ * time the rate the chip sustains for that instruction in its current power
+ * state: flop = workgroups * 8 * 32 * iters * 65536.  out: device, f32
+ * [workgroups * 8], one value per wave (its content is a checksum of no
+ * meaning).  1 <= workgroups <= 65536, 1 <= iters <= 2^24.
+ */
+jet_status jet_probe_mfma_rate(float* out, int32_t workgroups, int32_t iters,
+                               int32_t zero_data, void* stream);
+
 /* Text for a status code (static storage). */
 const char* jet_status_str(jet_status st);
 

@@ -48,6 +48,8 @@ def lib() -> ctypes.CDLL:
             f = getattr(L, name)
             f.restype = i32
             f.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp]
+        L.jet_probe_mfma_rate.restype = i32
+        L.jet_probe_mfma_rate.argtypes = [vp, i32, i32, i32, vp]
         L.jet_status_str.restype = ctypes.c_char_p
         L.jet_status_str.argtypes = [i32]
         L.jet_version.restype = i32
@@ -56,6 +58,10 @@ def lib() -> ctypes.CDLL:
 
 
 # ---------------------------------------------------------------- raw calls
+
+def jet_probe_mfma_rate(out, workgroups, iters, zero_data, stream) -> int:
+    return int(lib().jet_probe_mfma_rate(out, int(workgroups), int(iters), int(zero_data), stream))
+
 
 def jet_version() -> int:
     return int(lib().jet_version())
@@ -173,3 +179,22 @@ def fp8_linear_wgrad(qdyT, sdyT, qxT, sxT, out: torch.Tensor | None = None) -> t
     if st:
         raise JetError(st, "jet_fp8_linear_wgrad")
     return dw
+
+
+def probe_mfma_rate(workgroups: int = 1024, iters: int = 2000, zero_data: bool = False, repeats: int = 5) -> float:
+    """Measurement aid: sustained rate (flop/s) of the register-resident FP8 16x16x128
+    matrix-core stream of ``jet_probe_mfma_rate`` on the current device and stream."""
+    out = torch.empty((workgroups * 8,), dtype=torch.float32, device="cuda")
+    st = jet_probe_mfma_rate(_ptr(out), workgroups, max(iters // 10, 1), zero_data, _stream())   # warm-up
+    if st:
+        raise JetError(st, "jet_probe_mfma_rate")
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(repeats):
+        st = jet_probe_mfma_rate(_ptr(out), workgroups, iters, zero_data, _stream())
+        if st:
+            raise JetError(st, "jet_probe_mfma_rate")
+    b.record()
+    torch.cuda.synchronize()
+    flop = float(repeats) * workgroups * 8 * 32 * iters * 65536
+    return flop / (a.elapsed_time(b) * 1e-3)

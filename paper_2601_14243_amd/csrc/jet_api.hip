@@ -72,6 +72,13 @@ jet_status jet_fp8_linear_wgrad(const uint8_t* qdyT, const float* sdyT, const ui
     return gemm_entry(qdyT, sdyT, qxT, sxT, jet::kSbRow, dw, N, K, M, true, stream);
 }
 
+jet_status jet_probe_mfma_rate(float* out, int32_t workgroups, int32_t iters, int32_t zero_data, void* stream) {
+    if (!out) return JET_ERR_NULL;
+    if (workgroups < 1 || workgroups > 65536 || iters < 1 || iters > (1 << 24)) return JET_ERR_SHAPE;
+    if (misaligned(out)) return JET_ERR_ALIGN;
+    return after_launch(jet::launch_mfma_rate(out, workgroups, iters, zero_data != 0, static_cast<hipStream_t>(stream)));
+}
+
 const char* jet_status_str(jet_status st) {
     switch (st) {
         case JET_OK: return "ok";

@@ -90,3 +90,12 @@ def test_gemm_reduction_length_limit(L):
     assert b.jet_fp8_linear_fwd(A, A, A, A, A, 128, 128, big, None) == SHAPE       # K
     assert b.jet_fp8_linear_dgrad(A, A, A, A, A, 128, big, 128, None) == SHAPE     # N is DGrad's reduction
     assert b.jet_fp8_linear_wgrad(A, A, A, A, A, big, 128, 128, None) == SHAPE     # M is WGrad's reduction
+
+
+def test_probe_argument_errors(L):
+    from paper_2601_14243_amd import binding as b
+    assert b.jet_probe_mfma_rate(None, 8, 8, 0, None) == NULL
+    assert b.jet_probe_mfma_rate(A, 0, 8, 0, None) == SHAPE
+    assert b.jet_probe_mfma_rate(A, 8, 0, 0, None) == SHAPE
+    assert b.jet_probe_mfma_rate(A, 1 << 20, 8, 0, None) == SHAPE
+    assert b.jet_probe_mfma_rate(A + 4, 8, 8, 0, None) == ALIGN
