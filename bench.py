@@ -29,7 +29,7 @@ PEAK_FP8_TFLOPS = 5000.0     # MI355X dense FP8 MFMA peak
 # HBM-side bytes per average FProp/DGrad launch of this workload, from two rocprofv3 --pmc runs of
 # this script (FETCH_SIZE x 2.000 KiB, WRITE_SIZE x 1.000 KiB per count; the factors are what the
 # counters read for a plain 1 GiB copy): profiles/bench_8B_M16384_hbm_counters.txt
-TILE_GEMM_TRAFFIC_BYTES = (371213.7 * 2.0 + 187525.9 * 1.0) * 1024.0
+TILE_GEMM_TRAFFIC_BYTES = (371345.9 * 2.0 + 187573.6 * 1.0) * 1024
 PEAK_HBM_GBPS = 8000.0
 M_TRAIN = 16384
 DECODE_M = (1, 8, 32, 128)
@@ -194,24 +194,29 @@ def main():
 def sustained_mfma(torch, jet, achieved_flops):
     """Context for `frac`: the rate the same FP8 matrix-core instruction sustains on this machine
     from registers alone (no LDS, no memory), with pseudo-random and with all-zero operands,
-    and the shader clock rocm-smi shows meanwhile.  Operand values change the power the
+    and the shader clock the driver reports meanwhile (null if it is not readable).  Operand values change the power the
     matrix cores draw and with it the clock; the published peak is at the full 2.4 GHz."""
+    import glob
     import re
-    import subprocess
     import threading
 
     def sclk():
-        try:
-            o = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=20).stdout
-            m = re.search(r"sclk clock level:[^(]*\((\d+)Mhz\)", o)
-            return int(m.group(1)) if m else None
-        except Exception:
-            return None
+        # current shader clock from sysfs (the level marked '*'); no child process is started
+        best = None
+        for f in glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"):
+            try:
+                for line in open(f).read().splitlines():
+                    m = re.match(r"\s*\S+:\s*(\d+)\s*[Mm][Hh]z\s*\*", line)
+                    if m:
+                        best = max(best or 0, int(m.group(1)))
+            except OSError:
+                pass
+        return best
 
     res = {}
     for name, zero in (("random", False), ("zero", True)):
         clk = []
-        th = threading.Thread(target=lambda: clk.append(sclk()))
+        th = threading.Thread(target=lambda: (time.sleep(0.25), clk.append(sclk())))
         jet.probe_mfma_rate(workgroups=1024, iters=4000, zero_data=zero, repeats=3)    # bring the clock to its steady state
         th.start()
         r = jet.probe_mfma_rate(workgroups=1024, iters=4000, zero_data=zero, repeats=40)
