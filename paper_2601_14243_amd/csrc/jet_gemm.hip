@@ -110,7 +110,7 @@ struct TileCfg {
     static constexpr int kLdsBytes = kStages * kStageBytes;
     static constexpr int kOccupancy = 512 / kThreads;   // workgroups per CU
     static_assert(BM == 32 * kWaves && BN == 32 * kWaves, "copy schedule assumes BM = BN = 32 * waves");
-    static_assert(TM % 2 == 0 && TN % 2 == 0, "fragment double buffer and paired stores assume even TM, TN");
+    static_assert(TM % 2 == 0 && TN % 4 == 0, "fragment double buffer and 64-column stores assume even TM and TN a multiple of 4");
 };
 
 // Tiles of one persistent workgroup.  The hardware deals workgroup b to XCD b % 8.  The
@@ -311,6 +311,11 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
     for (int n = 0; n < TN; ++n) cf[n] = col_frag(0, n);
     xf[0] = row_frag(0, 0);
     load_scales(0, next);
+    // s = sa * sb of the coming step (block scales: one binary32 product per row tile), formed as
+    // soon as the scales are in, so that the top of a step never waits for the LDS
+    float sai_n[TM];
+#pragma unroll
+    for (int m = 0; m < TM; ++m) sai_n[m] = (SB_MODE == kSbBlock) ? next.a[m] * next.b_block : next.a[m];
 
     v4f acc[TM][TN];
 #pragma unroll
@@ -330,7 +335,7 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
         float sai[TM];
         v4f sbj[TN];
 #pragma unroll
-        for (int m = 0; m < TM; ++m) sai[m] = (SB_MODE == kSbBlock) ? next.a[m] * next.b_block : next.a[m];
+        for (int m = 0; m < TM; ++m) sai[m] = sai_n[m];
         if (SB_MODE != kSbBlock) load_col_scales(slot, sbj);
 
         v4f pr[kRing];
@@ -351,8 +356,11 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
             }
             if (t < kTiles) {
                 const int m = t / TN, n = t % TN;
-                if (n == 0 && m + 1 < TM) xf[(m + 1) & 1] = row_frag(slot, m + 1);
                 pr[t % kRing] = group_product(cf[n], xf[m & 1]);
+                // next row's fragment, fetched behind the MFMA: a fetch in front of it would be
+                // included in whatever LDS wait that MFMA's operands need
+                __builtin_amdgcn_sched_barrier(0);
+                if (n == 0 && m + 1 < TM) xf[(m + 1) & 1] = row_frag(slot, m + 1);
             }
             if (!kFmaFirst) scale_fmas();
             __builtin_amdgcn_sched_barrier(0);
@@ -365,6 +373,12 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
                 cur = after;                          // step q+2 goes into stage `slot`
                 xf[TM & 1] = row_frag(slot ^ 1, 0);   // TM even: the buffer the last row does not use
                 load_scales(slot ^ 1, next);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (t == kTiles - 1) {
+                // the scales fetched after the barrier are in by now (only later fetches are still out)
+#pragma unroll
+                for (int m = 0; m < TM; ++m) sai_n[m] = (SB_MODE == kSbBlock) ? next.a[m] * next.b_block : next.a[m];
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (t >= kSync && t < kTiles) {
@@ -382,28 +396,50 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
         if (++g < G) continue;
         g = 0;
 
-        // epilogue of tile k.  A lane holds row r, columns 4 c4 .. 4 c4 + 3 of each MFMA tile;
-        // two row-swaps between neighbouring column tiles give every lane 8 consecutive
-        // columns (16 bytes) and every row 64 contiguous bytes per store instruction.
+        // epilogue of tile k.  A lane holds row r, columns 4 c4 .. 4 c4 + 3 of each MFMA tile.  Two
+        // row-swaps between neighbouring column tiles give every lane 8 consecutive columns
+        // (16 bytes) and the four lanes of a row 64 contiguous bytes; exchanging the upper eight
+        // rows of one such pair of tiles with the lower eight rows of the next pair then gives
+        // every row a whole 128-byte line per store instruction (8 rows x 128 B instead of
+        // 16 rows x 64 B: half as many memory transactions).
         int i0, j0;
         tile_origin(k, i0, j0);
+        const bool upper = (r & 8) != 0;
 #pragma unroll
         for (int m = 0; m < TM; ++m) {
-            const int i = i0 + (wi * TM + m) * 16 + r;
 #pragma unroll
-            for (int n = 0; n < TN; n += 2) {
-                const uint32_t a0 = bf16_pack2(acc[m][n][0], acc[m][n][1]);
-                const uint32_t a1 = bf16_pack2(acc[m][n][2], acc[m][n][3]);
-                const uint32_t b0 = bf16_pack2(acc[m][n + 1][0], acc[m][n + 1][1]);
-                const uint32_t b1 = bf16_pack2(acc[m][n + 1][2], acc[m][n + 1][3]);
-                // lanes 16-31 and 48-63 of the first operand <-> lanes 0-15 and 32-47 of the second
-                const auto s0 = __builtin_amdgcn_permlane16_swap(a0, b0, false, false);
-                const auto s1 = __builtin_amdgcn_permlane16_swap(a1, b1, false, false);
-                const uint4 o = {s0[0], s1[0], s0[1], s1[1]};
-                const int j = j0 + (wj * TN + n + (c4 & 1)) * 16 + (c4 >> 1) * 8;
-                if (i < I) *reinterpret_cast<uint4*>(out + (size_t)i * J + j) = o;
-                acc[m][n] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
-                acc[m][n + 1] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+            for (int n = 0; n < TN; n += 4) {
+                uint32_t lo[4], hi[4];   // this lane's 16 bytes of column tiles n, n+1 and of n+2, n+3
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const int nn = n + 2 * half;
+                    const uint32_t a0 = bf16_pack2(acc[m][nn][0], acc[m][nn][1]);
+                    const uint32_t a1 = bf16_pack2(acc[m][nn][2], acc[m][nn][3]);
+                    const uint32_t b0 = bf16_pack2(acc[m][nn + 1][0], acc[m][nn + 1][1]);
+                    const uint32_t b1 = bf16_pack2(acc[m][nn + 1][2], acc[m][nn + 1][3]);
+                    // lanes 16-31 and 48-63 of the first operand <-> lanes 0-15 and 32-47 of the second
+                    const auto s0 = __builtin_amdgcn_permlane16_swap(a0, b0, false, false);
+                    const auto s1 = __builtin_amdgcn_permlane16_swap(a1, b1, false, false);
+                    uint32_t* d = half ? hi : lo;
+                    d[0] = s0[0]; d[1] = s1[0]; d[2] = s0[1]; d[3] = s1[1];
+                    acc[m][nn] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+                    acc[m][nn + 1] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+                }
+                uint4 first, second;     // rows 0-7 / rows 8-15 of the row tile, 64 columns each
+                uint32_t* f = &first.x;
+                uint32_t* g2 = &second.x;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    // row_ror:8 swaps the two halves of every 16-lane row: lane r sees lane r ^ 8
+                    const uint32_t hi_x = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)hi[e], 0x128, 0xf, 0xf, true);
+                    const uint32_t lo_x = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)lo[e], 0x128, 0xf, 0xf, true);
+                    f[e] = upper ? hi_x : lo[e];
+                    g2[e] = upper ? hi[e] : lo_x;
+                }
+                const int jc = j0 + (wj * TN + n + (c4 & 1)) * 16 + (c4 >> 1) * 8 + (upper ? 32 : 0);
+                const int ia = i0 + (wi * TM + m) * 16 + (r & 7);
+                if (ia < I) *reinterpret_cast<uint4*>(out + (size_t)ia * J + jc) = first;
+                if (ia + 8 < I) *reinterpret_cast<uint4*>(out + (size_t)(ia + 8) * J + jc) = second;
             }
         }
         ++k;
