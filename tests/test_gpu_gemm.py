@@ -83,6 +83,38 @@ def test_wgrad(jet, M, N, K):
     check_gemm(host_bits(dw), ref, f"wgrad {M}x{N}x{K}")
 
 
+def test_forward_ragged_rows_on_the_persistent_256_tile(jet):
+    """A batch that is large enough for the persistent 256x256 tile kernel but whose row count
+    is no multiple of 256 (nor of 128): the last tile row is partly empty.  Checked in full
+    against the oracle, including the last valid rows."""
+    M, N, K = 14500, 1024, 256                     # 57 x 4 tiles of 256 x 256, last row of tiles has 164 rows
+    x, w = ji.activations(M, K, 4711), ji.weights(N, K, 4712)
+    qa = orc.quant_act(x)
+    qw, sw = orc.quant_weight(w)
+    ref = orc.gemm(qa["q_row"], qa["s_row"], qw, sw)
+    y = host_bits(jet.fp8_linear_fwd(dev(qa["q_row"]), dev(qa["s_row"]), dev(qw), dev(sw)))
+    assert y.shape == (M, N)
+    # two groups only and activations with x50 outlier channels: a handful of heavily cancelling
+    # elements leave the quick allowance; they are held to the instruction's rigorous worst case
+    check_gemm(y, ref, f"fwd ragged {M}x{N}x{K}", operands=(qa["q_row"], qa["s_row"], qw, sw, False))
+    # the rows of the last, partly empty tile row agree with the oracle as often as all others
+    same = (y == ref["out"]).mean(axis=1)
+    assert abs(same[-164:].mean() - same[:-164].mean()) < 0.01
+
+
+def test_wgrad_half_filled_last_tile_row(jet):
+    """WGrad whose output row count N is a multiple of 128 but not of 256, at a size that
+    takes the 256x256 tile: the last tile row holds 128 valid rows."""
+    M, N, K = 256, 7552, 2048                      # output 7552 x 2048: 30 x 8 tiles, reduction over 256 tokens
+    dy, x = ji.grads(M, N, seed=91), ji.activations(M, K, seed=92)
+    qd = orc.quant_act(dy, row=False, col=True)
+    qx = orc.quant_act(x, row=False, col=True)
+    ref = orc.gemm(qd["q_colT"], qd["s_colT"], qx["q_colT"], qx["s_colT"], sb_mode=orc.SB_ROW)
+    dw = jet.fp8_linear_wgrad(dev(qd["q_colT"]), dev(qd["s_colT"]), dev(qx["q_colT"]), dev(qx["s_colT"]))
+    assert tuple(dw.shape) == (N, K)
+    check_gemm(host_bits(dw), ref, f"wgrad {M}x{N}x{K}")
+
+
 def test_full_backward_from_fp8_saved_activation(jet):
     """The backward pass as the method runs it: dY quantized both ways in one pass, the
     FP8-saved X re-quantized along tokens, then DGrad and WGrad -- all on the GPU,
