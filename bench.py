@@ -42,6 +42,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode-sweep", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the 32B-class GEMM pass and the weight re-quantization timing")
     return ap.parse_args()
 
 
@@ -184,11 +186,81 @@ def main():
     }
 
     out["roofline"].update(sustained_mfma(torch, jet, g_rate))
+    if not args.no_extras:
+        out["requantize_8B_layer"] = requant_timing(torch, jet, mats)
+    del mats
+    torch.cuda.empty_cache()
+    if not args.no_extras:
+        out["train_gemms_32B_M32768"] = train_gemms_32b(torch, jet)
     if not args.no_decode_sweep:
         out["decode"] = decode_sweep(torch, jet, layer)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))
+
+
+def _time(torch, fn, reps):
+    fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) * 1e-3 / reps
+
+
+def requant_timing(torch, jet, mats):
+    """Re-quantization of the seven weight matrices of the layer after an update (bf16 in, FP8
+    codes + 128x128 scales out), without and with the transposed copy that DGrad reads."""
+    nk = sum(m["N"] * m["K"] for m in mats)
+
+    def plain():
+        for m in mats:
+            jet.quant_weight(m["w"], out=(m["qw"][0], m["qw"][1]))
+
+    def both():
+        for m in mats:
+            jet.quant_weight(m["w"], transposed=True, out=m["qw"])
+
+    t1, t2 = _time(torch, plain, 10), _time(torch, both, 10)
+    return {"us_per_layer": round(t1 * 1e6, 1), "GB/s": round(nk * 3.0 / t1 / 1e9, 1),
+            "with_transposed_copy_us_per_layer": round(t2 * 1e6, 1),
+            "with_transposed_copy_GB/s": round(nk * 4.0 / t2 / 1e9, 1)}
+
+
+def train_gemms_32b(torch, jet):
+    """FProp, DGrad and WGrad of the seven 32B-class matrices at M = 32768 (long rollouts packed
+    into one training batch), GEMM kernels only, one matrix resident at a time."""
+    import jet_inputs as ji
+    dev, M = "cuda:0", 32768
+    gen = torch.Generator(device=dev)
+    t_tot, fl_tot, per = 0.0, 0.0, {}
+    for idx, (name, N, K) in enumerate(ji.LAYER_32B):
+        gen.manual_seed(4000 + idx)
+        x = torch.randn((M, K), generator=gen, device=dev).to(torch.bfloat16)
+        w = (torch.randn((N, K), generator=gen, device=dev) * 0.02).to(torch.bfloat16)
+        dy = (torch.randn((M, N), generator=gen, device=dev) * 1e-3).to(torch.bfloat16)
+        qx = jet.quant_act(x)
+        qxT = jet.quant_act(qx["q_row"], qx["s_row"], row=False, col=True)
+        qdy = jet.quant_act(dy, row=True, col=True)
+        qw = jet.quant_weight(w, transposed=True)
+        del x, w, dy
+        y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+        dx = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
+        dw = torch.empty((N, K), dtype=torch.bfloat16, device=dev)
+        t = (_time(torch, lambda: jet.fp8_linear_fwd(qx["q_row"], qx["s_row"], qw[0], qw[1], out=y), 3)
+             + _time(torch, lambda: jet.fp8_linear_dgrad(qdy["q_row"], qdy["s_row"], qw[2], qw[3], out=dx), 3)
+             + _time(torch, lambda: jet.fp8_linear_wgrad(qdy["q_colT"], qdy["s_colT"], qxT["q_colT"], qxT["s_colT"], out=dw), 3))
+        fl = 3 * 2.0 * M * N * K
+        per[name] = round(fl / t / 1e12, 1)
+        t_tot += t
+        fl_tot += fl
+        del qx, qxT, qdy, qw, y, dx, dw
+        torch.cuda.empty_cache()
+    return {"tflops": round(fl_tot / t_tot / 1e12, 1), "ms_per_layer": round(t_tot * 1e3, 2),
+            "frac_of_peak": round(fl_tot / t_tot / 1e12 / PEAK_FP8_TFLOPS, 4), "per_matrix_tflops": per}
 
 
 def sustained_mfma(torch, jet, achieved_flops):
