@@ -387,8 +387,10 @@ def cpu_baseline():
         return time.perf_counter() - t0
 
     N = K = 1024
-    t_small = run(128, N, K)
-    k = int(min(256, max(1, round(15.0 / max(t_small, 1e-3)))))
+    # two small runs separate the fixed part (weight quantization) from the cost per 128 rows
+    t1, t3 = run(128, N, K), run(384, N, K)
+    per = max((t3 - t1) / 2.0, 1e-3)
+    k = int(min(400, max(1, round((15.0 - max(t1 - per, 0.0)) / per))))
     M = 128 * k
     t = run(M, N, K)
     fl = 3 * 2 * M * N * K
