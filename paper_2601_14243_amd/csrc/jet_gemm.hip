@@ -73,7 +73,8 @@ __device__ __forceinline__ int xcd_contiguous_id(int b, int n) {
 //
 // Per step the operand tiles of one group (BM + BN rows x 128 bytes) go global->LDS
 // directly as whole cache lines, swizzled so that every fragment ds_read_b128 is
-// conflict-free.  Two LDS stages; step q lives in stage q & 1.
+// conflict-free.  S LDS stages (two; four for the small tile when there is at most one
+// workgroup per CU); step q lives in stage q % S and is copied S - 1 steps ahead.
 //
 // Pipeline of one step q (t counts the wave's MFMA tiles, row m = t / TN, column n = t % TN):
 //   top      : the column fragments cf[0..TN), the first row fragment and the scales of
@@ -99,16 +100,18 @@ __device__ __forceinline__ int xcd_contiguous_id(int b, int n) {
 // Both configurations have BM = BN = 32 * waves, so every wave copies 4 A blocks,
 // 4 B blocks and one scale line per step.
 // ------------------------------------------------------------------------
-template <int WI, int WJ, int TM, int TN>
+template <int WI, int WJ, int TM, int TN, int S = 2>
 struct TileCfg {
     static constexpr int kWaves = WI * WJ;
     static constexpr int kThreads = 64 * kWaves;
     static constexpr int BM = WI * TM * 16, BN = WJ * TN * 16;
     static constexpr int kABytes = BM * 128, kBBytes = BN * 128;
     static constexpr int kStageBytes = kABytes + kBBytes + (BM + BN) * 4;
-    static constexpr int kStages = 2;
+    static constexpr int kStages = S;                    // LDS stages: copies run kStages - 1 steps ahead
     static constexpr int kLdsBytes = kStages * kStageBytes;
-    static constexpr int kOccupancy = 512 / kThreads;   // workgroups per CU
+    static constexpr int kOccupancy =                    // workgroups per CU: by waves and by LDS
+        (512 / kThreads) < (160 * 1024 / kLdsBytes) ? (512 / kThreads) : (160 * 1024 / kLdsBytes);
+    static_assert((S & (S - 1)) == 0 && S >= 2 && kLdsBytes <= 160 * 1024, "stages");
     static_assert(BM == 32 * kWaves && BN == 32 * kWaves, "copy schedule assumes BM = BN = 32 * waves");
     static_assert(TM % 2 == 0 && TN % 4 == 0, "fragment double buffer and 64-column stores assume even TM and TN a multiple of 4");
 };
@@ -141,12 +144,12 @@ __device__ __forceinline__ uint32_t bf16_pack2(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-template <int SB_MODE, int WI, int WJ, int TM, int TN>
+template <int SB_MODE, int WI, int WJ, int TM, int TN, int S = 2>
 __global__ __launch_bounds__(64 * WI * WJ, 512 / (64 * WI * WJ))
 void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ sa,
                       const uint8_t* __restrict__ B, const float* __restrict__ sb,
                       uint16_t* __restrict__ out, int I, int J, int R, int tiles_i, int tiles_j) {
-    using C = TileCfg<WI, WJ, TM, TN>;
+    using C = TileCfg<WI, WJ, TM, TN, S>;
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_ptr_t)smem;
     const int t = threadIdx.x, w = t >> 6, l = t & 63, r = l & 15, c4 = l >> 4;
@@ -295,15 +298,19 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
     static_assert(kLate >= 1 && kLate <= kCopies && kCopies - kLate <= kSync, "copy slots");
 
     // ---- prologue: step 0 into stage 0, first copies of step 1, fragments of step 0 ----
+    // steps 0 .. S-2 whole, the first copies of step S-1; then wait for step 0 only
     Cursor cur = cursor_at_tile(0);
 #pragma unroll
-    for (int i = 0; i < kCopies; ++i) copy_one(cur, i, 0u);
-    cur = cursor_after(cur);
-    JET_WAIT_VMCNT(0);
+    for (int s = 0; s + 1 < S; ++s) {
+#pragma unroll
+        for (int i = 0; i < kCopies; ++i) copy_one(cur, i, (uint32_t)(s * C::kStageBytes));
+        cur = cursor_after(cur);
+    }
+#pragma unroll
+    for (int i = 0; i < kLate; ++i) copy_one(cur, i, (uint32_t)((S - 1) * C::kStageBytes));
+    JET_WAIT_VMCNT((S - 2) * kCopies + kLate);
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-#pragma unroll
-    for (int i = 0; i < kLate; ++i) copy_one(cur, i, (uint32_t)C::kStageBytes);
 
     v8i cf[TN], xf[2];
     RawScales next;
@@ -323,12 +330,12 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
 #pragma unroll
         for (int b = 0; b < TN; ++b) acc[a][b] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
 
-    // `cur` is the cursor of step q+1 at the top of step q
+    // `cur` is the cursor of step q+S-1 at the top of step q (its first copies are already issued)
     for (int q = 0, k = 0, g = 0; q < n_steps; ++q) {
-        const int slot = q & 1;
-        const Cursor after = cursor_after(cur);     // step q+2 (all control flow of a step is here)
+        const int slot = q & (S - 1), nslot = (q + 1) & (S - 1);
+        const Cursor after = cursor_after(cur);     // step q+S (all control flow of a step is here)
         const uint32_t st_this = __builtin_amdgcn_readfirstlane(slot * C::kStageBytes);
-        const uint32_t st_other = __builtin_amdgcn_readfirstlane((slot ^ 1) * C::kStageBytes);
+        const uint32_t st_other = __builtin_amdgcn_readfirstlane(((q + S - 1) & (S - 1)) * C::kStageBytes);
 
         // ---- one straight-line block from here to the end of the tile loop ----
         // scales of this step: s = sa * sb, one binary32 product per (row, column scale)
@@ -366,13 +373,13 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
             __builtin_amdgcn_sched_barrier(0);
             if (t == kSync) {
                 // every read of stage `slot` has returned (the MFMA above needed the last one);
-                // this wave's copies of step q+1 were issued about one step ago
-                JET_WAIT_VMCNT(0);
+                // of this wave's copies only those of steps q+2 .. q+S-1 may still be on their way
+                JET_WAIT_VMCNT((S - 2) * kCopies);
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
-                cur = after;                          // step q+2 goes into stage `slot`
-                xf[TM & 1] = row_frag(slot ^ 1, 0);   // TM even: the buffer the last row does not use
-                load_scales(slot ^ 1, next);
+                cur = after;                          // step q+S goes into stage `slot`
+                xf[TM & 1] = row_frag(nslot, 0);      // TM even: the buffer the last row does not use
+                load_scales(nslot, next);
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (t == kTiles - 1) {
@@ -382,14 +389,14 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (t >= kSync && t < kTiles) {
-                cf[t - kSync] = col_frag(slot ^ 1, t - kSync);   // its last MFMA of this step is issued
+                cf[t - kSync] = col_frag(nslot, t - kSync);      // its last MFMA of this step is issued
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (t > kSync) {
-                copy_one(cur, t - kSync - 1, st_this);   // copies 0 .. kLate-1 of step q+2
+                copy_one(cur, t - kSync - 1, st_this);   // copies 0 .. kLate-1 of step q+S
                 __builtin_amdgcn_sched_barrier(0);
             } else if (t < kCopies - kLate) {
-                copy_one(cur, kLate + t, st_other);   // remaining copies of step q+1
+                copy_one(cur, kLate + t, st_other);   // remaining copies of step q+S-1
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -829,12 +836,14 @@ static hipError_t allow_lds(K kernel, int bytes) {
 // big tile: 256x256, 8 waves of 128x64;  small tile: 128x128, 4 waves of 64x64
 #define JET_BIG 2, 4, 8, 4
 #define JET_SMALL 2, 2, 4, 4
+#define JET_SMALL_DEEP 2, 2, 4, 4, 4   /* four stages, one workgroup per CU: copies three steps ahead */
 #define JET_STRIP_SMALL 2, 2, 4, 4   /* 32-row blocks, two workgroups per CU */
 #define JET_STRIP_WIDE 4, 2, 7, 5    /* 64-row blocks */
 using StripSmall = StripCfg<JET_STRIP_SMALL>;
 using StripWide = StripCfg<JET_STRIP_WIDE>;
 using BigCfg = TileCfg<JET_BIG>;
 using SmallCfg = TileCfg<JET_SMALL>;
+using SmallDeepCfg = TileCfg<JET_SMALL_DEEP>;
 
 template <int SB_MODE>
 static hipError_t launch_tile(const uint8_t* A, const float* sa, const uint8_t* B, const float* sb,
@@ -851,6 +860,14 @@ static hipError_t launch_tile(const uint8_t* A, const float* sa, const uint8_t* 
                            (int)R, ti, tj);
     } else {
         const int ti = (int)((I + 127) / 128), tj = (int)(J / 128);
+        if ((long)ti * tj <= cus) {
+            // at most one workgroup per CU anyway: spend the LDS on two more stages, so that operands
+            // that come from HBM (decode batches against cold weights) are fetched three steps ahead
+            hipLaunchKernelGGL((gemm_tile_kernel<SB_MODE, JET_SMALL_DEEP>), dim3((unsigned)(ti * tj)),
+                               dim3(SmallDeepCfg::kThreads), SmallDeepCfg::kLdsBytes, st, A, sa, B, sb, o, (int)I,
+                               (int)J, (int)R, ti, tj);
+            return hipGetLastError();
+        }
         const long wgs = std::min<long>((long)ti * tj, (long)cus * SmallCfg::kOccupancy);
         hipLaunchKernelGGL((gemm_tile_kernel<SB_MODE, JET_SMALL>), dim3((unsigned)wgs),
                            dim3(SmallCfg::kThreads), SmallCfg::kLdsBytes, st, A, sa, B, sb, o, (int)I,
@@ -868,6 +885,8 @@ hipError_t launch_gemm(const uint8_t* A, const float* sa, const uint8_t* B, cons
         if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbRow, JET_BIG>, BigCfg::kLdsBytes);
         if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbBlock, JET_SMALL>, SmallCfg::kLdsBytes);
         if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbRow, JET_SMALL>, SmallCfg::kLdsBytes);
+        if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbBlock, JET_SMALL_DEEP>, SmallDeepCfg::kLdsBytes);
+        if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbRow, JET_SMALL_DEEP>, SmallDeepCfg::kLdsBytes);
         if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<6, 4, 1>, sk_lds_bytes(6, 4, 1));
         if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<3, 8, 1>, sk_lds_bytes(3, 8, 1));
         if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<1, 8, 1>, sk_lds_bytes(1, 8, 1));
@@ -899,7 +918,7 @@ hipError_t launch_gemm(const uint8_t* A, const float* sa, const uint8_t* B, cons
         return hipGetLastError();
     }
     // batches of 65-256 rows against a wide weight matrix (a hundred 128x128 tiles or more) are
-    // faster on the tile kernel (measured, gate/up 14336x4096: 39 against 45 us at 128 rows, 40
+    // faster on the tile kernel (measured, gate/up 14336x4096: 30 against 45 us at 128 rows, 30
     // against 74 us at 256 rows); narrower ones (4096 columns) stay on the strip kernel
     const bool wide_batch = I > 64 && ((I + 127) / 128) * (J / 128) >= 100;
     if (I <= 256 && sb_mode == kSbBlock && !wide_batch) {
