@@ -29,7 +29,7 @@ PEAK_FP8_TFLOPS = 5000.0     # MI355X dense FP8 MFMA peak
 # HBM-side bytes per average FProp/DGrad launch of this workload, from two rocprofv3 --pmc runs of
 # this script (FETCH_SIZE x 2.000 KiB, WRITE_SIZE x 1.000 KiB per count; the factors are what the
 # counters read for a plain 1 GiB copy): profiles/bench_8B_M16384_hbm_counters.txt
-TILE_GEMM_TRAFFIC_BYTES = (371369.4 * 2.0 + 187245.7 * 1.0) * 1024
+TILE_GEMM_TRAFFIC_BYTES = (371317.0 * 2.0 + 187245.7 * 1.0) * 1024
 PEAK_HBM_GBPS = 8000.0
 M_TRAIN = 16384
 DECODE_M = (1, 8, 32, 128)
