@@ -586,19 +586,21 @@ __global__ __launch_bounds__(64 * kSkWaves) void gemm_skinny_kernel(const uint8_
 
 // ------------------------------------------------------------------------
 // Strip kernel for decode batches, 16 < I <= 256 (block scales only).  The weights are
-// streamed once per 64-row block of the batch, so the kernel lives on memory-level
-// parallelism, not on the matrix core.  A workgroup of 4 waves (one per SIMD) owns a
-// (16 RM) x (16 CN) output tile and walks the whole reduction two groups (a "pair") at
-// a time.  The weight rows (from HBM) and the activation rows + scales (L2-resident)
-// travel global->LDS through two separate rings, a deep one for the weights and a
-// shallower one for the activations.  The outstanding-copy counter of a wave retires in
-// issue order, so a wave that issued both streams could never keep the weights further
-// ahead than the activations: waves 0 and 1 copy only weights, waves 2 and 3 only
-// activations and scales (four dedicated copy waves next to the four computing ones, so that
-// no MFMA stream ever waits behind a copy).  One barrier per pair; the fragments of pair p+2 are fetched from
-// LDS into registers while pair p is computed, so neither the LDS latency nor the barrier
-// is paid per group.  Wave w owns RM*CN/4 of the MFMA tiles and runs their ordered fma
-// chains in registers: the same chain as every other kernel, so rows are bit-identical.
+// streamed once per row block of the batch, so the kernel lives on memory-level
+// parallelism, not on the matrix core.  A workgroup of 8 waves owns a (16 RM) x (16 CN)
+// output tile and walks the whole reduction two groups (a "pair") at a time.  Waves 0-3
+// (one per SIMD) compute; waves 4-7 only copy, so that no MFMA stream ever waits behind
+// a copy.  The weight rows and scale lines (from HBM) and the activation rows
+// (L2-resident) travel global->LDS through two separate rings.  The outstanding-copy
+// counter of a wave retires in issue order, so a wave that issued both streams could
+// never keep the weights further ahead than the activations: waves 4 and 5 copy only
+// weights and scales, waves 6 and 7 only activations.  One barrier per pair; the
+// fragments of pair p+2 are fetched from LDS into registers while pair p is computed, so
+// neither the LDS latency nor the barrier is paid per group.  Computing wave w owns
+// RM*CN/4 of the MFMA tiles and runs their ordered fma chains in registers: the same chain
+// as every other kernel, so rows are bit-identical.
+// Two configurations: 32-row blocks with rings shallow enough for two workgroups per CU
+// (they cover each other's start-up and drain), 64-row blocks with deep rings.
 // ------------------------------------------------------------------------
 template <int RM, int CN, int WDEPTH, int ADEPTH>
 struct StripCfg {
