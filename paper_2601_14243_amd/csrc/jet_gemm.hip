@@ -455,14 +455,14 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
 }
 
 // ------------------------------------------------------------------------
-// Skinny kernel for I <= 16 (decode): bound by streaming B (the weights) once.
-// A workgroup of 4 waves owns 16 output columns and the whole reduction.  The
-// groups are dealt to the waves in runs of 8; every wave streams its own units
-// (16 weight rows + the 16 or 32 activation rows + scales of one group) through
-// a private LDS ring with kSkDepth units in flight, using the same whole-line
-// LDS-DMA and swizzled fragment layout as the tile kernel -- no barrier is needed
-// for the ring.  Every 32 (16) groups the p_g and s_g meet in LDS and four waves per row
-// tile run the ordered fma chain for their quarter of the outputs.
+// Skinny kernel for I <= 32 (decode): bound by streaming B (the weights) once.
+// A workgroup of kSkWaves waves owns 16 output columns and the whole reduction.  The
+// groups of a pass (32 / RM groups) are dealt to the waves in runs of consecutive
+// groups; every wave streams its own units (16 weight rows + the 16 or 32 activation
+// rows + scales of one group) through a private LDS ring with kSkDepth units in flight,
+// using the same whole-line LDS-DMA and swizzled fragment layout as the tile kernel --
+// no barrier is needed for the ring.  After every pass the p_g and s_g meet in LDS and
+// four waves per row tile run the ordered fma chain for their quarter of the outputs.
 // ------------------------------------------------------------------------
 constexpr int sk_unit_bytes(int rm) { return 2048 + rm * 2048 + 256; }    // weight fragment, RM activation fragments, scales
 constexpr int sk_group_bytes(int rm) { return rm * (4 * 64 * 4 + 64 * 4); } // per row tile: p[4][64] + s[64]
