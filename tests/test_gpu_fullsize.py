@@ -125,6 +125,15 @@ def test_32b_k_proj_training_step_long_rollout(jet):
     _layer_case(jet, 4, 1, ji.LAYER_32B, 32768, 16)
 
 
+def test_32b_gate_proj_forward_long_rollout(jet):
+    _layer_case(jet, 4, 4, ji.LAYER_32B, 32768, 8, do_dgrad=False, do_wgrad=False)
+
+
+def test_32b_down_proj_forward_long_rollout(jet):
+    # the longest reduction of the configurations: K = 27648 (216 groups), X is 1.8 GB of bf16
+    _layer_case(jet, 4, 6, ji.LAYER_32B, 32768, 6, do_dgrad=False, do_wgrad=False)
+
+
 @pytest.mark.parametrize("idx", [0, 6])           # q_proj 5120x5120, down_proj 5120x27648
 @pytest.mark.parametrize("M", [1, 64, 256])
 def test_32b_decode(jet, idx, M):
