@@ -611,7 +611,14 @@ struct StripCfg {
     static constexpr int kAGroup = RM * 2048;                   // activation fragments
     static constexpr int kWStage = 2 * kWGroup, kAStage = 2 * kAGroup;
     static constexpr int kSinkBytes = 256;                      // landing zone of the L2 warm-up loads
-    static constexpr int kLdsBytes = kWDepth * kWStage + kADepth * kAStage + kSinkBytes;
+    // 64-row blocks fetch the activation scales a chunk of 16 groups ahead, [row][16 groups], into
+    // three chunk buffers (the one being read, the next one, and the one being filled); 32-row
+    // blocks fetch one scale per row with every group (measured: the chunks gain 15 % on 64-row
+    // blocks with a long reduction and lose 10 % on 32-row blocks with a short one)
+    static constexpr bool kSaAhead = BM == 64;
+    static constexpr int kSaChunk = 16, kSaBufBytes = BM * kSaChunk * 4, kSaBufs = 3;
+    static constexpr int kSaOffset = kWDepth * kWStage + kADepth * kAStage + kSinkBytes;
+    static constexpr int kLdsBytes = kSaOffset + (kSaAhead ? kSaBufs * kSaBufBytes : 0);
     static constexpr int kWOps = 2 * (CN + 1), kAOps = 2 * RM;  // copies per wave per pair
     static constexpr int kTiles = RM * CN / kWaves;             // MFMA tiles per wave
     static constexpr int kNM = (kTiles + CN - 1) / CN;          // distinct row tiles per wave
@@ -620,6 +627,9 @@ struct StripCfg {
     static_assert(RM % 2 == 0 && CN % 2 == 0 && RM * CN % kWaves == 0 && BM <= 64 && 128 % BN == 0, "");
     static_assert(kNM * kNN == kTiles, "a wave's tiles form a kNM x kNN rectangle");
     static_assert(kWDepth >= 4 && kADepth >= 4 && (kWDepth - 3) * kWOps < 64 && (kADepth - 3) * kAOps < 64, "");
+    // Iteration p fills the buffer of chunk (2 (p + kWDepth) + 1) / 16 + 1 while the reads are at group
+    // 2 p + 4 or later: the chunk that buffer held (three chunks back) must be behind every read.
+    static_assert(kSaChunk == 16 && BM / 4 <= kSaChunk && (!kSaAhead || 2 * kWDepth + 1 < kSaChunk + 6), "");
     static_assert(kLdsBytes <= 160 * 1024, "");
 };
 
@@ -672,12 +682,24 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const uint8_t* __restri
             off[i] = (uint32_t)row * (uint32_t)R + (lane_chunk ^ ((blk & 1) * 64));
         }
     }
-    // scale lines travel with the weights (the weight waves have far fewer copies to issue than
-    // the activation waves): wave 4 copies sa of the tile's rows (up to 64), wave 5 the block scale
-    const float* gs = (w == 4) ? sa + (size_t)min(i0 + l, I - 1) * G : sb + (size_t)(j0 >> 7) * G;
+    // scales travel with the weights (the weight waves have far fewer copies to issue than the
+    // activation waves).  Wave 5 copies the block scale of every group.  Wave 4 copies the
+    // activation scales: one per row with every group, or (kSaAhead) a chunk of 16 groups ahead:
+    // with group g it fetches 4 rows x the 16 groups of the next chunk (4 cache lines per
+    // instruction instead of one per lane), so the chunk after g's is complete before its
+    // first group is.
+    const float* sb_line = sb + (size_t)(j0 >> 7) * G;
+    const float* sa_line = sa + (size_t)min(i0 + l, I - 1) * G;
+    const int sa_row = l >> 4, sa_grp = l & 15;
     const uint32_t lds_w = __builtin_amdgcn_readfirstlane(lds0 + side * kWMine * 1024);
     const uint32_t lds_a = __builtin_amdgcn_readfirstlane(lds0 + C::kWDepth * C::kWStage + side * kAMine * 1024);
     const uint32_t lds_s = __builtin_amdgcn_readfirstlane(lds0 + CN * 2048 + side * 256);
+    const uint32_t lds_sa = __builtin_amdgcn_readfirstlane(lds0 + C::kSaOffset);
+    // rows 4 rq .. 4 rq + 3 of the tile (past the end: the last row), groups of chunk c (past the end: the last group)
+    auto copy_sa = [&](int c, int rq) {
+        const int row = min(i0 + 4 * rq + sa_row, I - 1), grp = min(C::kSaChunk * c + sa_grp, G - 1);
+        dma4(lds_sa + (c % C::kSaBufs) * C::kSaBufBytes + rq * 256, sa + (size_t)row * G + grp);
+    };
     // this wave's copies of pair p (groups past the end repeat the last one)
     auto issue = [&](int p) {
 #pragma unroll
@@ -687,7 +709,9 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const uint8_t* __restri
                 const uint32_t st = (p % C::kWDepth) * C::kWStage + h * C::kWGroup;
 #pragma unroll
                 for (int i = 0; i < kWMine; ++i) dma16(lds_w + st + i * 1024, baseW + (size_t)g * kGroup, off[i]);
-                dma4(lds_s + st, gs + g);
+                if (w == 5) dma4(lds_s + st, sb_line + g);
+                else if (C::kSaAhead) copy_sa(g / C::kSaChunk + 1, (g % C::kSaChunk) % (C::BM / 4));
+                else dma4(lds_s + st, sa_line + g);
             } else {
                 const uint32_t st = (p % C::kADepth) * C::kAStage + h * C::kAGroup;
 #pragma unroll
@@ -708,6 +732,8 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const uint8_t* __restri
     auto fetch = [&](int p, Operands& o) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
+            const int g = min(2 * p + h, G - 1);
+            const uint8_t* ps = smem + C::kSaOffset + ((g / C::kSaChunk) % C::kSaBufs) * C::kSaBufBytes + (g % C::kSaChunk) * 4;
             const uint8_t* pw = smem + (p % C::kWDepth) * C::kWStage + h * C::kWGroup;
             const uint8_t* pa = smem + C::kWDepth * C::kWStage + (p % C::kADepth) * C::kAStage + h * C::kAGroup;
 #pragma unroll
@@ -716,7 +742,9 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const uint8_t* __restri
 #pragma unroll
             for (int m = 0; m < C::kNM; ++m) {
                 o.xf[h][m] = load_frag(pa + (m0 + m) * 2048 + frag_lo, pa + (m0 + m) * 2048 + frag_hi);
-                o.sa[h][m] = *reinterpret_cast<const float*>(pw + CN * 2048 + ((m0 + m) * 16 + r) * 4);
+                o.sa[h][m] = C::kSaAhead
+                                 ? *reinterpret_cast<const float*>(ps + ((m0 + m) * 16 + r) * (C::kSaChunk * 4))
+                                 : *reinterpret_cast<const float*>(pw + CN * 2048 + ((m0 + m) * 16 + r) * 4);
             }
             o.sb[h] = *reinterpret_cast<const float*>(pw + CN * 2048 + 256);
         }
@@ -774,6 +802,11 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const uint8_t* __restri
     // ---- prologue: fill both rings, fetch pairs 0 and 1 ----
     // iteration p of the main loop issues pair p + depth; the prologue issues pairs 0 .. depth-1
     // in the same relative order, so the steady-state counts hold from the start
+    if (C::kSaAhead && !copier) {
+        // chunk 0 of the activation scales: the computing waves have nothing else to do yet
+        for (int rq = w; rq < C::BM / 4; rq += C::kWaves) copy_sa(0, rq);
+        JET_WAIT_VMCNT(0);
+    }
     for (int v = 0; v < C::kWDepth; ++v)
         if (copier && (w_stream || v < C::kADepth)) issue(v);
     if (copier) wait_copies(C::kWDepth - 2);         // pairs 0 and 1 landed: depth-2 later pairs outstanding
