@@ -623,13 +623,12 @@ struct StripCfg {
     static constexpr int kTiles = RM * CN / kWaves;             // MFMA tiles per wave
     static constexpr int kNM = (kTiles + CN - 1) / CN;          // distinct row tiles per wave
     static constexpr int kNN = kTiles < CN ? kTiles : CN;       // distinct column tiles per wave
-    static constexpr int kFetchOps = 2 * (2 * (kNM + kNN) + kNM + 1);   // LDS reads of one pair
     static_assert(RM % 2 == 0 && CN % 2 == 0 && RM * CN % kWaves == 0 && BM <= 64 && 128 % BN == 0, "");
     static_assert(kNM * kNN == kTiles, "a wave's tiles form a kNM x kNN rectangle");
-    static_assert(kWDepth >= 4 && kADepth >= 4 && (kWDepth - 3) * kWOps < 64 && (kADepth - 3) * kAOps < 64, "");
-    // Iteration p fills the buffer of chunk (2 (p + kWDepth) + 1) / 16 + 1 while the reads are at group
-    // 2 p + 4 or later: the chunk that buffer held (three chunks back) must be behind every read.
-    static_assert(kSaChunk == 16 && BM / 4 <= kSaChunk && (!kSaAhead || 2 * kWDepth + 1 < kSaChunk + 6), "");
+    static_assert(kWDepth >= 3 && kADepth >= 3 && (kWDepth + 1) * kWOps < 64 && (kADepth + 1) * kAOps < 64, "");
+    // Iteration p fills the buffer of chunk (2 (p + kWDepth + 1) + 1) / 16 + 1 while the reads are at
+    // group 2 p + 4 or later: the chunk that buffer held (three chunks back) must be behind every read.
+    static_assert(kSaChunk == 16 && BM / 4 <= kSaChunk && (!kSaAhead || 2 * kWDepth + 3 < kSaChunk + 6), "");
     static_assert(kLdsBytes <= 160 * 1024, "");
 };
 
@@ -770,17 +769,10 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const uint8_t* __restri
             }
         }
     };
-    // "my copies of all pairs up to the one issued `back` issue() calls ago have landed"
-    auto wait_copies = [&](int back) {
-        if (w_stream) {
-            if (back == C::kWDepth - 3) JET_WAIT_VMCNT((C::kWDepth - 3) * C::kWOps);
-            else if (back == C::kWDepth - 2) JET_WAIT_VMCNT((C::kWDepth - 2) * C::kWOps);
-            else JET_WAIT_VMCNT(0);
-        } else {
-            if (back == C::kWDepth - 3) JET_WAIT_VMCNT((C::kADepth - 3) * C::kAOps);
-            else if (back == C::kWDepth - 2) JET_WAIT_VMCNT((C::kADepth - 2) * C::kAOps);
-            else JET_WAIT_VMCNT(0);
-        }
+    // "of my copies only those of the last depth - 2 pairs I issued may still be on their way"
+    auto wait_copies = [&]() {
+        if (w_stream) JET_WAIT_VMCNT((C::kWDepth - 2) * C::kWOps);
+        else JET_WAIT_VMCNT((C::kADepth - 2) * C::kAOps);
     };
 
     // ---- L2 warm-up of this row block's activations ----
@@ -809,17 +801,24 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const uint8_t* __restri
     }
     for (int v = 0; v < C::kWDepth; ++v)
         if (copier && (w_stream || v < C::kADepth)) issue(v);
-    if (copier) wait_copies(C::kWDepth - 2);         // pairs 0 and 1 landed: depth-2 later pairs outstanding
+    if (copier) wait_copies();                       // pairs 0 and 1 landed: depth-2 later pairs outstanding
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    // iteration p (one barrier): pairs <= p+2 have landed; the slots of pair p are free (its
-    // fragments are in registers).  The two kinds of wave run the same number of barriers.
+    // The computing waves now take pairs 0 and 1 into registers; a second barrier, and the slots of
+    // pairs 0 and 1 are free.  Iteration p (one barrier): pairs <= p+2 have landed; pairs p and p+1
+    // are in registers, pair p+2 is being fetched into registers, so the slots of pair p+1 are
+    // refilled (with pair p+1+depth): depth - 1 pairs are in flight, one slot is being read.
+    // The two kinds of wave run the same number of barriers.
     if (copier) {
+        const int depth = w_stream ? C::kWDepth : C::kADepth;
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        issue(depth);
         for (int p = 0; p < P; ++p) {
-            wait_copies(C::kWDepth - 3);
+            wait_copies();
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
-            issue(p + (w_stream ? C::kWDepth : C::kADepth));
+            issue(p + depth + 1);
         }
         JET_WAIT_VMCNT(0);   // nothing may be in flight towards the LDS when it is released
         return;
@@ -827,14 +826,16 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const uint8_t* __restri
     Operands op0, op1, op2;
     fetch(0, op0);
     fetch(min(1, P - 1), op1);
+    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
     auto iteration = [&](int p, const Operands& cur, Operands& nxt2) {
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         fetch(min(p + 2, P - 1), nxt2);
         compute(p, cur);
-        // my reads of pair p+1's slots are done before the next barrier lets them be overwritten
-        // (LDS reads return in order: at most the reads of pair p+2 stay outstanding)
-        __builtin_amdgcn_s_waitcnt(0xc07f | ((C::kFetchOps < 15 ? C::kFetchOps : 15) << 8));
+        // my reads of pair p+2's slots are done before the next barrier lets them be overwritten
+        __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
     };
     int p = 0;
     for (; p + 2 < P; p += 3) {
