@@ -126,6 +126,36 @@ jet_status jet_fp8_linear_wgrad(const uint8_t* qdyT, const float* sdyT,
                                 void* stream);
 
 /*
+ * Fused producers (Sec. 4.2: the quantization of an activation is fused with
+ * the operator in front of the GEMM; Sec. 4.3 names RMSNorm and the activation
+ * function).  The operator is evaluated with bf16 module semantics and its
+ * result h goes straight to the 1x128 row quantizer: q_row u8 [M,K], s_row f32
+ * [M,K/128] are bit-identical to jet_quant_act on a stored bf16 h, which is
+ * never written.  K % 128 == 0; any M >= 1.
+ *
+ * RMSNorm:  h[m,k] = bf16( gamma[k] * bf16( x[m,k] * r[m] ) ),
+ *           r[m] = 1 / sqrt( mean_k x[m,k]^2 + eps ).
+ * x bf16 [M,K], gamma bf16 [K], eps >= 0 finite (else JET_ERR_ARG).  The mean
+ * is formed in binary64 and rounded once to binary32; the rest is binary32.
+ * K <= 32768 (a row is held in the registers of one workgroup).  A row of
+ * zeros with eps == 0 has no defined result.
+ */
+jet_status jet_rmsnorm_quant(const void* x, const void* gamma, float eps,
+                             int64_t M, int64_t K,
+                             uint8_t* q_row, float* s_row, void* stream);
+
+/*
+ * SiLU(gate) * up:  a = bf16( g / (1 + e^-g) ), the real function rounded once;
+ *                   h = bf16( a * u ), a binary32 product.
+ * gate, up: bf16 [M,K] with a common row stride ld >= K in elements, ld % 8 ==
+ * 0 (ld = K for two dense tensors, ld = 2K for the two halves of a fused
+ * gate/up projection output).
+ */
+jet_status jet_silu_mul_quant(const void* gate, const void* up, int64_t ld,
+                              int64_t M, int64_t K,
+                              uint8_t* q_row, float* s_row, void* stream);
+
+/*
  * Measurement aid for benchmarks; not a step of the layer.  Launches
  * `workgroups` workgroups of 8 waves that each issue 32 * iters FP8 16x16x128
  * matrix-core instructions on register operands (pseudo-random finite E4M3

@@ -98,6 +98,21 @@ def grads(M: int, N: int, seed: int) -> np.ndarray:
     return f32_to_bf16_bits(g)
 
 
+def norm_weight(K: int, seed: int) -> np.ndarray:
+    """RMSNorm weight [K] bf16 bits: 1 + N(0, std 0.1)."""
+    return f32_to_bf16_bits(np.float32(1.0) + _normal_f32(_rng(seed), (K,), 0.1))
+
+
+def mlp_intermediate(M: int, K: int, seed: int) -> np.ndarray:
+    """One [M,2K] bf16 array holding the gate (columns 0..K-1) and up (K..2K-1) projections of an
+    MLP block: N(0, std 2) with 0.5% of the entries scaled by 8."""
+    rng = _rng(seed)
+    h = _normal_f32(rng, (M, 2 * K), 2.0)
+    mask = rng.random(size=(M, 2 * K), dtype=np.float32) < np.float32(0.005)
+    h[mask] *= np.float32(8.0)
+    return f32_to_bf16_bits(h)
+
+
 def weight_update(w_bits: np.ndarray, seed: int) -> np.ndarray:
     """Synthetic optimizer step on the bf16 master weights: W + N(0, std 1e-4)."""
     w = bf16_bits_to_f32(w_bits)

@@ -66,6 +66,14 @@ def lib() -> ctypes.CDLL:
             f = getattr(L, name)
             f.restype = i32
             f.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp]
+        L.orc_bf16_from_double.restype = ctypes.c_uint16
+        L.orc_bf16_from_double.argtypes = [ctypes.c_double]
+        L.orc_silu_bf16.restype = ctypes.c_uint16
+        L.orc_silu_bf16.argtypes = [ctypes.c_uint16]
+        L.orc_rmsnorm.restype = i32
+        L.orc_rmsnorm.argtypes = [vp, vp, ctypes.c_float, i64, i64, vp]
+        L.orc_silu_mul.restype = i32
+        L.orc_silu_mul.argtypes = [vp, vp, i64, i64, i64, vp]
         _lib = L
     return _lib
 
@@ -211,3 +219,57 @@ def fp8_linear_wgrad(qdyT, sdyT, qxT, sxT):
     N, M = np.shape(qdyT)
     K = np.shape(qxT)[0]
     return _named(lib().orc_fp8_linear_wgrad, qdyT, sdyT, qxT, sxT, M, N, K, (N, K))
+
+
+# ---------------------------------------------------------- fused producers
+
+def bf16_from_double(v: float) -> int:
+    return int(lib().orc_bf16_from_double(float(v)))
+
+
+def silu_bf16(g_bits: int) -> int:
+    """bf16( silu(g) ) for one bf16 bit pattern."""
+    return int(lib().orc_silu_bf16(int(g_bits)))
+
+
+def rmsnorm(x, gamma, eps):
+    """h = bf16(gamma * bf16(x * rsqrt(mean(x^2) + eps))) as bf16 bits [M,K]."""
+    x, gamma = _c(x, np.uint16), _c(gamma, np.uint16)
+    M, K = x.shape
+    if gamma.shape != (K,):
+        raise ValueError("gamma must have K elements")
+    h = np.empty((M, K), np.uint16)
+    _check(lib().orc_rmsnorm(_p(x), _p(gamma), float(eps), M, K, _p(h)))
+    return h
+
+
+def silu_mul(gate, up):
+    """h = bf16(bf16(silu(gate)) * up) as bf16 bits [M,K]; gate and up may be views of one
+    [M, 2K] array (equal row strides)."""
+    gate, up = np.asarray(gate), np.asarray(up)
+    if gate.dtype != np.uint16 or up.dtype != np.uint16 or gate.shape != up.shape:
+        raise ValueError("gate and up must be uint16 arrays of one shape")
+    M, K = gate.shape
+    if gate.strides != up.strides or gate.strides[1] != 2 or gate.strides[0] % 2:
+        raise ValueError("gate and up need unit column stride and a common row stride")
+    ld = gate.strides[0] // 2
+    h = np.empty((M, K), np.uint16)
+    _check(lib().orc_silu_mul(gate.ctypes.data_as(ctypes.c_void_p), up.ctypes.data_as(ctypes.c_void_p),
+                              ld, M, K, _p(h)))
+    return h
+
+
+def rmsnorm_quant(x, gamma, eps):
+    """RMSNorm, then the 1x128 row quantizer on its bf16 output."""
+    h = rmsnorm(x, gamma, eps)
+    out = quant_act(h)
+    out["h"] = h
+    return out
+
+
+def silu_mul_quant(gate, up):
+    """SiLU(gate) * up, then the 1x128 row quantizer on its bf16 output."""
+    h = silu_mul(gate, up)
+    out = quant_act(h)
+    out["h"] = h
+    return out

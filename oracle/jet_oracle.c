@@ -16,7 +16,9 @@
  * torch's float8_e4m3fn CPU conversion, exhaustive bf16-amax scale sweep,
  * lossless integer GEMM against int64 arithmetic, exact rational brute force
  * on tiny shapes, fp64 dequantise-then-matmul, transpose / permutation /
- * power-of-two metamorphic invariants.
+ * power-of-two metamorphic invariants; for the fused producers: closed forms
+ * (one-hot rows, constant rows, scale invariance), a binary64 numpy evaluation,
+ * and torch's binary64 silu over every finite bf16 input.
  *
  * Build: gcc -O2 -std=c11 -fopenmp -fPIC -shared (no -ffast-math: every
  * division, multiplication and fma below must be the IEEE binary32 operation).
@@ -376,6 +378,96 @@ int orc_fp8_linear_wgrad(const uint8_t* qdyT, const float* sdyT, const uint8_t* 
                          uint16_t* dw) {
     return orc_gemm(qdyT, sdyT, qxT, sxT, ORC_SB_ROW, N, K, M, NULL, 0, NULL, 0, acc, dw, NULL,
                     NULL, NULL);
+}
+
+/* ------------------------------------------------------ fused producers -- */
+
+/* The paper fuses the 1x128 activation quantization with the operator in front of
+ * the GEMM (Sec. 4.2) and names RMSNorm and the activation function as those
+ * operators (Sec. 4.3); it does not spell out their arithmetic.  The reading taken
+ * here is the usual bf16 module semantics: the operator produces a bf16 tensor h,
+ * and h is then quantized exactly as any other activation (orc_quant_act).  The
+ * functions below produce h; the tests chain them with orc_quant_act. */
+
+/* double -> bf16, one rounding to nearest (ties to even), also into the bf16
+ * subnormal range (quantum 2^-133); magnitudes that round to 2^128 give infinity. */
+uint16_t orc_bf16_from_double(double v) {
+    uint16_t sign = (uint16_t)(signbit(v) ? 0x8000u : 0u);
+    if (isnan(v)) return (uint16_t)(sign | 0x7FC0u);
+    double a = fabs(v);
+    if (a == 0.0) return sign;
+    if (isinf(a)) return (uint16_t)(sign | 0x7F80u);
+    int ex;
+    (void)frexp(a, &ex);
+    int e = ex - 1;                       /* floor(log2 a) */
+    if (e < -126) e = -126;
+    double quantum = ldexp(1.0, e - 7);   /* spacing of bf16 values in this binade */
+    double r = nearbyint(a / quantum) * quantum;   /* exact scaling, RNE to an integer, exact product */
+    if (r >= ldexp(1.0, 128)) return (uint16_t)(sign | 0x7F80u);
+    float f = (float)r;                   /* exact: r has at most 8 significant bits */
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    return (uint16_t)(sign | (u >> 16));
+}
+
+/* RMSNorm:  h[m,k] = bf16( gamma[k] * bf16( x[m,k] * r[m] ) ),
+ *           r[m]   = 1 / sqrt( mean_k x[m,k]^2 + eps ).
+ * The mean is formed in binary64 (every square of a bf16 value is exact there) and
+ * rounded once to binary32; adding eps, the square root, the reciprocal and the two
+ * products are single binary32 operations; both bf16 roundings are to nearest even. */
+int orc_rmsnorm(const uint16_t* x, const uint16_t* gamma, float eps, int64_t M, int64_t K, uint16_t* h) {
+    if (!x || !gamma || !h) return ORC_ERR_NULL;
+    if (M < 1 || K < 1) return ORC_ERR_SHAPE;
+    if (!(eps >= 0.0f) || !isfinite(eps)) return ORC_ERR_ARG;
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t m = 0; m < M; ++m) {
+        double ss = 0.0;
+        for (int64_t k = 0; k < K; ++k) {
+            double v = (double)orc_bf16_to_f32(x[m * K + k]);
+            if (!isfinite(v)) bad = 1;
+            ss += v * v;
+        }
+        volatile float ms = (float)(ss / (double)K);
+        volatile float d = ms + eps;
+        volatile float rt = sqrtf(d);
+        volatile float r = 1.0f / rt;
+        if (!isfinite(r) || !isfinite(ms)) bad = 1;   /* an all-zero row with eps = 0; a mean beyond binary32 */
+        for (int64_t k = 0; k < K; ++k) {
+            volatile float n = orc_bf16_to_f32(x[m * K + k]) * r;
+            float nb = orc_bf16_to_f32(orc_bf16_rne(n));
+            volatile float t = orc_bf16_to_f32(gamma[k]) * nb;
+            h[m * K + k] = orc_bf16_rne(t);
+        }
+    }
+    return bad ? ORC_ERR_NONFINITE : ORC_OK;
+}
+
+/* SiLU(gate) * up:  a = bf16( g / (1 + e^-g) )  (the real function, rounded once),
+ *                   h = bf16( a * u )           (binary32 product, rounded to bf16).
+ * gate and up are bf16 [M,K] with a common row stride ld >= K (in elements), so that the
+ * two halves of a fused gate/up projection output can be passed without a copy. */
+uint16_t orc_silu_bf16(uint16_t g_bits) {
+    double g = (double)orc_bf16_to_f32(g_bits);
+    return orc_bf16_from_double(g / (1.0 + exp(-g)));
+}
+
+int orc_silu_mul(const uint16_t* gate, const uint16_t* up, int64_t ld, int64_t M, int64_t K, uint16_t* h) {
+    if (!gate || !up || !h) return ORC_ERR_NULL;
+    if (M < 1 || K < 1 || ld < K) return ORC_ERR_SHAPE;
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t k = 0; k < K; ++k) {
+            float g = orc_bf16_to_f32(gate[m * ld + k]), u = orc_bf16_to_f32(up[m * ld + k]);
+            if (!isfinite(g) || !isfinite(u)) bad = 1;
+            float a = orc_bf16_to_f32(orc_silu_bf16(gate[m * ld + k]));
+            volatile float t = a * u;
+            if (!isfinite(t)) bad = 1;
+            h[m * K + k] = orc_bf16_rne(t);
+        }
+    }
+    return bad ? ORC_ERR_NONFINITE : ORC_OK;
 }
 
 /* vector helpers for the tests */

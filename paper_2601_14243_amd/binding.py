@@ -48,6 +48,10 @@ def lib() -> ctypes.CDLL:
             f = getattr(L, name)
             f.restype = i32
             f.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, vp]
+        L.jet_rmsnorm_quant.restype = i32
+        L.jet_rmsnorm_quant.argtypes = [vp, vp, ctypes.c_float, i64, i64, vp, vp, vp]
+        L.jet_silu_mul_quant.restype = i32
+        L.jet_silu_mul_quant.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp]
         L.jet_probe_mfma_rate.restype = i32
         L.jet_probe_mfma_rate.argtypes = [vp, i32, i32, i32, vp]
         L.jet_status_str.restype = ctypes.c_char_p
@@ -91,6 +95,14 @@ def jet_fp8_linear_wgrad(qdyT, sdyT, qxT, sxT, dw, M, N, K, stream) -> int:
     return int(lib().jet_fp8_linear_wgrad(qdyT, sdyT, qxT, sxT, dw, M, N, K, stream))
 
 
+def jet_rmsnorm_quant(x, gamma, eps, M, K, q_row, s_row, stream) -> int:
+    return int(lib().jet_rmsnorm_quant(x, gamma, float(eps), M, K, q_row, s_row, stream))
+
+
+def jet_silu_mul_quant(gate, up, ld, M, K, q_row, s_row, stream) -> int:
+    return int(lib().jet_silu_mul_quant(gate, up, ld, M, K, q_row, s_row, stream))
+
+
 # ------------------------------------------------------- tensor conveniences
 
 def _stream() -> int:
@@ -127,6 +139,43 @@ def quant_act(x: torch.Tensor, x_scales: torch.Tensor | None = None, row: bool =
                        _stream())
     if st:
         raise JetError(st, "jet_quant_act")
+    return o
+
+
+def _row_pair(M, K, dev, out):
+    o = {} if out is None else out
+    if "q_row" not in o:
+        o["q_row"] = torch.empty((M, K), dtype=torch.uint8, device=dev)
+        o["s_row"] = torch.empty((M, max(K // GROUP, 1)), dtype=torch.float32, device=dev)
+    return o
+
+
+def rmsnorm_quant(x: torch.Tensor, gamma: torch.Tensor, eps: float, out: dict | None = None) -> dict:
+    """RMSNorm of bf16 [M,K] with bf16 weight [K], written as 1x128 FP8: dict(q_row, s_row)."""
+    _need(x, torch.bfloat16, "x")
+    M, K = x.shape
+    if not gamma.is_cuda or not gamma.is_contiguous() or gamma.dtype != torch.bfloat16 or gamma.shape != (K,):
+        raise TypeError("gamma: need a contiguous CUDA bf16 tensor of K elements")
+    o = _row_pair(M, K, x.device, out)
+    st = jet_rmsnorm_quant(_ptr(x), _ptr(gamma), eps, M, K, _ptr(o["q_row"]), _ptr(o["s_row"]), _stream())
+    if st:
+        raise JetError(st, "jet_rmsnorm_quant")
+    return o
+
+
+def silu_mul_quant(gate: torch.Tensor, up: torch.Tensor, out: dict | None = None) -> dict:
+    """SiLU(gate) * up of two bf16 [M,K] tensors (contiguous, or the two halves of one
+    contiguous [M,2K] tensor), written as 1x128 FP8: dict(q_row, s_row)."""
+    for t, name in ((gate, "gate"), (up, "up")):
+        if not t.is_cuda or t.dtype != torch.bfloat16 or t.dim() != 2 or t.stride(1) != 1:
+            raise TypeError(f"{name}: need a 2-D CUDA bf16 tensor with unit column stride")
+    if gate.shape != up.shape or gate.stride(0) != up.stride(0):
+        raise TypeError("gate and up need one shape and one row stride")
+    M, K = gate.shape
+    o = _row_pair(M, K, gate.device, out)
+    st = jet_silu_mul_quant(_ptr(gate), _ptr(up), gate.stride(0), M, K, _ptr(o["q_row"]), _ptr(o["s_row"]), _stream())
+    if st:
+        raise JetError(st, "jet_silu_mul_quant")
     return o
 
 

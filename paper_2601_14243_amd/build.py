@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libjet.so")
-SOURCES = ["jet_api.hip", "jet_quant.hip", "jet_gemm.hip", "jet_probe.hip"]
+SOURCES = ["jet_api.hip", "jet_quant.hip", "jet_fused.hip", "jet_gemm.hip", "jet_probe.hip"]
 HEADERS = ["jet_internal.h", "jet_numerics.h", os.path.join("..", "..", "include", "jet.h")]
 
 # No fast-math: divisions, products and fmas must be the IEEE binary32 operations.

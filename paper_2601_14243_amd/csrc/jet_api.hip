@@ -72,6 +72,24 @@ jet_status jet_fp8_linear_wgrad(const uint8_t* qdyT, const float* sdyT, const ui
     return gemm_entry(qdyT, sdyT, qxT, sxT, jet::kSbRow, dw, N, K, M, true, stream);
 }
 
+jet_status jet_rmsnorm_quant(const void* x, const void* gamma, float eps, int64_t M, int64_t K,
+                             uint8_t* q_row, float* s_row, void* stream) {
+    if (!x || !gamma || !q_row || !s_row) return JET_ERR_NULL;
+    if (!(eps >= 0.0f) || eps > 3.0e38f) return JET_ERR_ARG;   /* negative, NaN or infinite */
+    if (M < 1 || K < 1 || K % 128 || K > 32768 || M > INT32_MAX / 2) return JET_ERR_SHAPE;
+    if (misaligned(x) || misaligned(gamma) || misaligned(q_row) || misaligned(s_row)) return JET_ERR_ALIGN;
+    return after_launch(jet::launch_rmsnorm_quant(x, gamma, eps, M, K, q_row, s_row, static_cast<hipStream_t>(stream)));
+}
+
+jet_status jet_silu_mul_quant(const void* gate, const void* up, int64_t ld, int64_t M, int64_t K,
+                              uint8_t* q_row, float* s_row, void* stream) {
+    if (!gate || !up || !q_row || !s_row) return JET_ERR_NULL;
+    if (M < 1 || K < 1 || K % 128 || ld < K || ld % 8) return JET_ERR_SHAPE;
+    if (M > INT32_MAX / 2 || K > INT32_MAX / 2 || ld > INT32_MAX / 2) return JET_ERR_SHAPE;
+    if (misaligned(gate) || misaligned(up) || misaligned(q_row) || misaligned(s_row)) return JET_ERR_ALIGN;
+    return after_launch(jet::launch_silu_mul_quant(gate, up, ld, M, K, q_row, s_row, static_cast<hipStream_t>(stream)));
+}
+
 jet_status jet_probe_mfma_rate(float* out, int32_t workgroups, int32_t iters, int32_t zero_data, void* stream) {
     if (!out) return JET_ERR_NULL;
     if (workgroups < 1 || workgroups > 65536 || iters < 1 || iters > (1 << 24)) return JET_ERR_SHAPE;
@@ -91,6 +109,6 @@ const char* jet_status_str(jet_status st) {
     return "unknown status";
 }
 
-int jet_version(void) { return 100; }
+int jet_version(void) { return 101; }
 
 }  // extern "C"

@@ -1,0 +1,176 @@
+// Fused producers: the operator in front of a GEMM writes its output directly as
+// 1x128-quantized FP8 (Jet-RL Sec. 4.2: the activation quantization is fused with the
+// previous operator; Sec. 4.3 names RMSNorm and the activation function).  The operator's
+// bf16 result h is never stored: it is rounded to bf16 in registers and quantized with the
+// row quantizer's arithmetic (jet_numerics.h), so the FP8 bytes and scales equal those of
+// "operator in bf16, then jet_quant_act".  Both kernels are HBM-bound streams.
+#include <algorithm>
+
+#include "jet_internal.h"
+#include "jet_numerics.h"
+
+namespace jet {
+
+// ------------------------------------------------------------------------
+// bf16 of a binary64 value with one rounding (finite input).  The conversion to binary32
+// is monotonic, so the binary32 value lies on the same side of every bf16 tie point as the
+// binary64 one -- unless it landed exactly on a tie, where the binary64 value decides.
+// ------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t bf16_from_double(double v) {
+    const float f = (float)v;
+    const uint32_t u = __float_as_uint(f);
+    if ((u & 0xffffu) == 0x8000u) {
+        const double fd = (double)f;
+        if (fd != v) return (u >> 16) + (fabs(v) > fabs(fd) ? 1u : 0u);
+    }
+    return bf16_rne(f);
+}
+
+// bf16( g / (1 + e^-g) ) of a bf16 value g, the real function rounded once.  binary32
+// arithmetic is within 3 ulp of the real value for |g| <= 80 and results above 2^-100;
+// when that cannot decide the bf16 rounding (the binary32 result is within 64 ulp of a tie)
+// and outside that range, binary64 arithmetic decides.
+__device__ __forceinline__ uint32_t silu_bf16(float g) {
+    const float a = g / (1.0f + expf(-g));
+    const uint32_t low = __float_as_uint(a) & 0xffffu;
+    const bool near_tie = (low - (0x8000u - 64u)) <= 128u;
+    const bool in_range = fabsf(g) <= 80.0f && fabsf(a) >= 0x1p-100f;
+    if (near_tie || !in_range) {
+        const double gd = (double)g;
+        return bf16_from_double(gd / (1.0 + exp(-gd)));
+    }
+    return bf16_rne(a);
+}
+
+// quantize the 16 values of a lane (a team of 8 lanes holds one 128-group) and store them
+__device__ __forceinline__ void quantize_store(float (&v)[16], uint8_t* q16, float* s1, bool leader) {
+    float am = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) am = fmaxf(am, fabsf(v[i]));
+    am = team8_max(am);
+    const GroupScale gs = make_scale(am);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v[i] = div_by_scale(v[i], gs);
+    uint4 o;
+    o.x = e4m3_pack4(v[0], v[1], v[2], v[3]);
+    o.y = e4m3_pack4(v[4], v[5], v[6], v[7]);
+    o.z = e4m3_pack4(v[8], v[9], v[10], v[11]);
+    o.w = e4m3_pack4(v[12], v[13], v[14], v[15]);
+    *reinterpret_cast<uint4*>(q16) = o;
+    if (leader) *s1 = gs.S;
+}
+
+__device__ __forceinline__ void unpack16(const uint16_t* p, float (&v)[16]) {
+    const uint4* p4 = reinterpret_cast<const uint4*>(p);
+    const uint4 u0 = p4[0], u1 = p4[1];
+    const uint32_t w[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        v[2 * i] = bf16_lo(w[i]);
+        v[2 * i + 1] = bf16_hi(w[i]);
+    }
+}
+
+// ------------------------------------------------------------------------
+// SiLU(gate) * up -> 1x128 FP8.  a = bf16(silu(g)), h = bf16(a * u) (binary32 product).
+// Same decomposition as the row quantizer: a team of 8 lanes owns a group, a lane 16
+// consecutive elements (2 x 32 B in, 16 B out).  gate and up share the row stride ld.
+// ------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void silu_mul_quant_kernel(const uint16_t* __restrict__ gate,
+                                                             const uint16_t* __restrict__ up, long ld,
+                                                             int groups_per_row, long n_groups,
+                                                             uint8_t* __restrict__ q, float* __restrict__ s) {
+    const long n_teams = (long)gridDim.x * 32;
+    const int l8 = threadIdx.x & 7;
+    for (long g = ((long)blockIdx.x * 256 + threadIdx.x) >> 3; g < n_groups; g += n_teams) {
+        const long m = g / groups_per_row;
+        const long src = m * ld + (g - m * groups_per_row) * kGroup + l8 * 16;
+        float a[16], u[16];
+        unpack16(gate + src, a);
+        unpack16(up + src, u);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float act = __uint_as_float(silu_bf16(a[i]) << 16);
+            a[i] = __uint_as_float(bf16_rne(act * u[i]) << 16);
+        }
+        quantize_store(a, q + g * kGroup + l8 * 16, s + g, l8 == 0);
+    }
+}
+
+// ------------------------------------------------------------------------
+// RMSNorm -> 1x128 FP8.  One workgroup per row; a thread keeps its 16-element pieces of the
+// row (one per 4096 columns) in registers between the two phases:
+//   1. sum of squares in binary64 (the square of a bf16 value is exact there), reduced over
+//      the workgroup; mean rounded once to binary32; r = 1 / sqrt(mean + eps) in binary32;
+//   2. n = bf16(x r), h = bf16(gamma n), quantized per 128-group.
+// ------------------------------------------------------------------------
+template <int MAXCH>
+__global__ __launch_bounds__(256) void rmsnorm_quant_kernel(const uint16_t* __restrict__ x,
+                                                            const uint16_t* __restrict__ gamma, float eps,
+                                                            int K, uint8_t* __restrict__ q,
+                                                            float* __restrict__ s) {
+    __shared__ double part[4];
+    const int t = threadIdx.x, l8 = t & 7;
+    const long m = blockIdx.x;
+    const uint16_t* row = x + m * K;
+    float v[MAXCH][16];
+    double ss = 0.0;
+#pragma unroll
+    for (int c = 0; c < MAXCH; ++c) {
+        const int k0 = c * 4096 + t * 16;
+        if (k0 < K) {
+            unpack16(row + k0, v[c]);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) ss = fma((double)v[c][i], (double)v[c][i], ss);
+        }
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) ss += __shfl_xor(ss, d, 64);
+    if ((t & 63) == 0) part[t >> 6] = ss;
+    __syncthreads();
+    const double total = (part[0] + part[1]) + (part[2] + part[3]);
+    const float ms = (float)(total / (double)K);
+    const float r = 1.0f / sqrtf(ms + eps);
+#pragma unroll
+    for (int c = 0; c < MAXCH; ++c) {
+        const int k0 = c * 4096 + t * 16;
+        if (k0 < K) {   // whole teams: K is a multiple of 128
+            float gm[16];
+            unpack16(gamma + k0, gm);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float n = __uint_as_float(bf16_rne(v[c][i] * r) << 16);
+                v[c][i] = __uint_as_float(bf16_rne(gm[i] * n) << 16);
+            }
+            quantize_store(v[c], q + m * K + k0, s + (m * K + k0) / kGroup, l8 == 0);
+        }
+    }
+}
+
+// ----------------------------------------------------------------- launch --
+
+hipError_t launch_silu_mul_quant(const void* gate, const void* up, long ld, long M, long K, uint8_t* q,
+                                 float* s, hipStream_t st) {
+    const long n_groups = M * (K / kGroup);
+    const long blocks = std::min<long>((n_groups + 31) / 32, 256L * 64);
+    hipLaunchKernelGGL(silu_mul_quant_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+                       static_cast<const uint16_t*>(gate), static_cast<const uint16_t*>(up), ld,
+                       (int)(K / kGroup), n_groups, q, s);
+    return hipGetLastError();
+}
+
+hipError_t launch_rmsnorm_quant(const void* x, const void* gamma, float eps, long M, long K, uint8_t* q,
+                                float* s, hipStream_t st) {
+    const uint16_t* xp = static_cast<const uint16_t*>(x);
+    const uint16_t* gp = static_cast<const uint16_t*>(gamma);
+    const int chunks = (int)((K + 4095) / 4096);
+#define JET_RMS(N) hipLaunchKernelGGL(rmsnorm_quant_kernel<N>, dim3((unsigned)M), dim3(256), 0, st, xp, gp, eps, (int)K, q, s)
+    if (chunks <= 1) JET_RMS(1);
+    else if (chunks <= 2) JET_RMS(2);
+    else if (chunks <= 4) JET_RMS(4);
+    else JET_RMS(8);
+#undef JET_RMS
+    return hipGetLastError();
+}
+
+}  // namespace jet

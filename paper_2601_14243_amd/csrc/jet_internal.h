@@ -16,6 +16,12 @@ hipError_t launch_quant_act(const void* x, const float* xs, int src, long M, lon
 hipError_t launch_quant_weight(const void* w, long N, long K, uint8_t* q, float* s, uint8_t* qT,
                                float* sT, hipStream_t st);
 
+// fused producers: h = SiLU(gate) * up or RMSNorm(x), in bf16 semantics, written as 1x128 FP8
+hipError_t launch_silu_mul_quant(const void* gate, const void* up, long ld, long M, long K, uint8_t* q,
+                                 float* s, hipStream_t st);
+hipError_t launch_rmsnorm_quant(const void* x, const void* gamma, float eps, long M, long K, uint8_t* q,
+                                float* s, hipStream_t st);
+
 // OUT[i,j] = sum_r A[i,r] B[j,r]; A u8 [I,R] with sa f32 [I,R/128]; B u8 [J,R] with sb as
 // sb_mode says; out bf16 [I,J].  I >= 1 arbitrary, J % 128 == 0, R % 128 == 0.
 hipError_t launch_gemm(const uint8_t* A, const float* sa, const uint8_t* B, const float* sb,

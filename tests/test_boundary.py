@@ -25,7 +25,8 @@ def _declared():
 def test_header_symbols_are_exported(L):
     names = _declared()
     assert {"jet_quant_act", "jet_quant_weight", "jet_fp8_linear_fwd", "jet_fp8_linear_dgrad",
-            "jet_fp8_linear_wgrad", "jet_status_str", "jet_version"} <= set(names)
+            "jet_fp8_linear_wgrad", "jet_rmsnorm_quant", "jet_silu_mul_quant", "jet_status_str",
+            "jet_version"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
@@ -90,6 +91,26 @@ def test_gemm_reduction_length_limit(L):
     assert b.jet_fp8_linear_fwd(A, A, A, A, A, 128, 128, big, None) == SHAPE       # K
     assert b.jet_fp8_linear_dgrad(A, A, A, A, A, 128, big, 128, None) == SHAPE     # N is DGrad's reduction
     assert b.jet_fp8_linear_wgrad(A, A, A, A, A, big, 128, 128, None) == SHAPE     # M is WGrad's reduction
+
+
+def test_fused_producer_argument_errors(L):
+    from paper_2601_14243_amd import binding as b
+    assert b.jet_rmsnorm_quant(None, A, 1e-6, 4, 128, A, A, None) == NULL
+    assert b.jet_rmsnorm_quant(A, A, 1e-6, 4, 128, A, None, None) == NULL
+    assert b.jet_rmsnorm_quant(A, A, -1.0, 4, 128, A, A, None) == ARG
+    assert b.jet_rmsnorm_quant(A, A, float("nan"), 4, 128, A, A, None) == ARG
+    assert b.jet_rmsnorm_quant(A, A, float("inf"), 4, 128, A, A, None) == ARG
+    assert b.jet_rmsnorm_quant(A, A, 1e-6, 0, 128, A, A, None) == SHAPE
+    assert b.jet_rmsnorm_quant(A, A, 1e-6, 4, 100, A, A, None) == SHAPE
+    assert b.jet_rmsnorm_quant(A, A, 1e-6, 4, 32768 + 128, A, A, None) == SHAPE      # a row no longer fits one workgroup
+    assert b.jet_rmsnorm_quant(A, A + 2, 1e-6, 4, 128, A, A, None) == ALIGN
+    assert b.jet_silu_mul_quant(None, A, 128, 4, 128, A, A, None) == NULL
+    assert b.jet_silu_mul_quant(A, A, 128, 4, 128, None, A, None) == NULL
+    assert b.jet_silu_mul_quant(A, A, 128, 0, 128, A, A, None) == SHAPE
+    assert b.jet_silu_mul_quant(A, A, 128, 4, 192, A, A, None) == SHAPE
+    assert b.jet_silu_mul_quant(A, A, 64, 4, 128, A, A, None) == SHAPE               # ld < K
+    assert b.jet_silu_mul_quant(A, A, 132, 4, 128, A, A, None) == SHAPE              # ld % 8
+    assert b.jet_silu_mul_quant(A, A + 8, 256, 4, 128, A, A, None) == ALIGN
 
 
 def test_probe_argument_errors(L):
