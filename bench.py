@@ -191,6 +191,7 @@ def main():
     del mats
     torch.cuda.empty_cache()
     if not args.no_extras:
+        out["fused_producers_8B_M16384"] = fused_producers(torch, jet, M)
         out["train_gemms_32B_M32768"] = train_gemms_32b(torch, jet)
     if not args.no_decode_sweep:
         out["decode"] = decode_sweep(torch, jet, layer)
@@ -228,6 +229,48 @@ def requant_timing(torch, jet, mats):
     return {"us_per_layer": round(t1 * 1e6, 1), "GB/s": round(nk * 3.0 / t1 / 1e9, 1),
             "with_transposed_copy_us_per_layer": round(t2 * 1e6, 1),
             "with_transposed_copy_GB/s": round(nk * 4.0 / t2 / 1e9, 1)}
+
+
+def fused_producers(torch, jet, M):
+    """The two operators in front of the layer's GEMMs writing FP8 directly (8B-class shapes):
+    RMSNorm of the hidden states [M,4096] and SiLU(gate)*up of one [M,2*14336] projection output.
+    GB/s = algorithmic bytes (bf16 in, codes + scales out) / time; the plain row quantizer on a
+    stored bf16 tensor of the same shape is timed beside each."""
+    dev = "cuda:0"
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(777)
+    res = {}
+    K = 4096
+    # three tensors in turn (0.6 GB of traffic per round): no pass finds its input in the 256 MB memory-side cache
+    xs = [torch.randn((M, K), generator=gen, device=dev).to(torch.bfloat16) for _ in range(3)]
+    gamma = (1.0 + 0.1 * torch.randn((K,), generator=gen, device=dev)).to(torch.bfloat16)
+    os_ = [jet.rmsnorm_quant(x, gamma, 1e-6) for x in xs]
+
+    def fused():
+        for x, o in zip(xs, os_):
+            jet.rmsnorm_quant(x, gamma, 1e-6, out=o)
+
+    def plain():
+        for x, o in zip(xs, os_):
+            jet.quant_act(x, out=o)
+
+    t, tq = _time(torch, fused, 10) / 3, _time(torch, plain, 10) / 3
+    by = M * K * (2 + 1 + 4 / 128)
+    res["rmsnorm_quant"] = {"us": round(t * 1e6, 1), "GB/s": round(by / t / 1e9, 1),
+                            "row_quantizer_alone_us": round(tq * 1e6, 1)}
+    x, o = None, None
+    del xs, os_
+    del x, o
+    K = 14336
+    gu = (torch.randn((M, 2 * K), generator=gen, device=dev) * 2.0).to(torch.bfloat16)
+    o = jet.silu_mul_quant(gu[:, :K], gu[:, K:])
+    t = _time(torch, lambda: jet.silu_mul_quant(gu[:, :K], gu[:, K:], out=o), 10)
+    h = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
+    tq = _time(torch, lambda: jet.quant_act(h, out=o), 10)
+    by = M * K * (4 + 1 + 4 / 128)
+    res["silu_mul_quant"] = {"us": round(t * 1e6, 1), "GB/s": round(by / t / 1e9, 1),
+                             "row_quantizer_alone_us": round(tq * 1e6, 1)}
+    return res
 
 
 def train_gemms_32b(torch, jet):

@@ -26,14 +26,20 @@ __device__ __forceinline__ uint32_t bf16_from_double(double v) {
     return bf16_rne(f);
 }
 
-// bf16( g / (1 + e^-g) ) of a bf16 value g, the real function rounded once.  binary32
-// arithmetic is within 3 ulp of the real value for |g| <= 80 and results above 2^-100;
-// when that cannot decide the bf16 rounding (the binary32 result is within 64 ulp of a tie)
-// and outside that range, binary64 arithmetic decides.
+// bf16( g / (1 + e^-g) ) of a bf16 value g, the real function rounded once.
+// Fast path in binary32: e^-g = 2^y with y = -g log2(e) split as -g c_hi (exact: 8 x 16
+// significant bits) plus a small remainder folded in as a factor 1 + ln2 * (-g c_lo); the
+// hardware 2^y and reciprocal are good to 1 ulp each, so the result is within 5 ulp of the
+// real value for |g| <= 80 and results above 2^-100.  Where that cannot decide the bf16
+// rounding (the binary32 result is within 8 ulp of a tie), and outside that range, binary64
+// arithmetic decides.  The function has 65280 finite inputs; the tests check every one.
 __device__ __forceinline__ uint32_t silu_bf16(float g) {
-    const float a = g / (1.0f + expf(-g));
+    const float c_hi = 0x1.7154p+0f, c_lo = 0x1.d94aep-18f, ln2 = 0x1.62e43p-1f;
+    const float p2 = __builtin_amdgcn_exp2f(-g * c_hi);
+    const float e = __builtin_fmaf(p2, (-g * c_lo) * ln2, p2);
+    const float a = g * __builtin_amdgcn_rcpf(1.0f + e);
     const uint32_t low = __float_as_uint(a) & 0xffffu;
-    const bool near_tie = (low - (0x8000u - 64u)) <= 128u;
+    const bool near_tie = (low - (0x8000u - 8u)) <= 16u;
     const bool in_range = fabsf(g) <= 80.0f && fabsf(a) >= 0x1p-100f;
     if (near_tie || !in_range) {
         const double gd = (double)g;
@@ -89,58 +95,73 @@ __global__ __launch_bounds__(256) void silu_mul_quant_kernel(const uint16_t* __r
         unpack16(gate + src, a);
         unpack16(up + src, u);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const float act = __uint_as_float(silu_bf16(a[i]) << 16);
-            a[i] = __uint_as_float(bf16_rne(act * u[i]) << 16);
+        for (int i = 0; i < 16; i += 2) {
+            const float act0 = __uint_as_float(silu_bf16(a[i]) << 16);
+            const float act1 = __uint_as_float(silu_bf16(a[i + 1]) << 16);
+            const uint32_t h2 = bf16_pack2(act0 * u[i], act1 * u[i + 1]);
+            a[i] = bf16_lo(h2);
+            a[i + 1] = bf16_hi(h2);
         }
         quantize_store(a, q + g * kGroup + l8 * 16, s + g, l8 == 0);
     }
 }
 
 // ------------------------------------------------------------------------
-// RMSNorm -> 1x128 FP8.  One workgroup per row; a thread keeps its 16-element pieces of the
-// row (one per 4096 columns) in registers between the two phases:
+// RMSNorm -> 1x128 FP8.  A team of kTeam threads owns a row and keeps it in registers
+// between the two phases (a thread holds 16-element pieces, one per 16 kTeam columns):
 //   1. sum of squares in binary64 (the square of a bf16 value is exact there), reduced over
-//      the workgroup; mean rounded once to binary32; r = 1 / sqrt(mean + eps) in binary32;
+//      the team; mean rounded once to binary32; r = 1 / sqrt(mean + eps) in binary32;
 //   2. n = bf16(x r), h = bf16(gamma n), quantized per 128-group.
+// kTeam = 64 (a wave per row, four rows per workgroup, no barrier, up to 128 bytes per lane in
+// flight) for rows up to 8192 columns; kTeam = 256 (the workgroup, one barrier) beyond.
 // ------------------------------------------------------------------------
-template <int MAXCH>
+template <int kTeam, int MAXCH>
 __global__ __launch_bounds__(256) void rmsnorm_quant_kernel(const uint16_t* __restrict__ x,
                                                             const uint16_t* __restrict__ gamma, float eps,
-                                                            int K, uint8_t* __restrict__ q,
+                                                            long M, int K, uint8_t* __restrict__ q,
                                                             float* __restrict__ s) {
     __shared__ double part[4];
     const int t = threadIdx.x, l8 = t & 7;
-    const long m = blockIdx.x;
+    const int lane = (kTeam == 64) ? (t & 63) : t;
+    const long m = (kTeam == 64) ? (long)blockIdx.x * 4 + (t >> 6) : (long)blockIdx.x;
+    if (m >= M) return;                                  // whole waves; only with a wave per row
     const uint16_t* row = x + m * K;
     float v[MAXCH][16];
     double ss = 0.0;
 #pragma unroll
     for (int c = 0; c < MAXCH; ++c) {
-        const int k0 = c * 4096 + t * 16;
+        const int k0 = (c * kTeam + lane) * 16;
+        if (k0 < K) unpack16(row + k0, v[c]);
+    }
+#pragma unroll
+    for (int c = 0; c < MAXCH; ++c) {
+        const int k0 = (c * kTeam + lane) * 16;
         if (k0 < K) {
-            unpack16(row + k0, v[c]);
 #pragma unroll
             for (int i = 0; i < 16; ++i) ss = fma((double)v[c][i], (double)v[c][i], ss);
         }
     }
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) ss += __shfl_xor(ss, d, 64);
-    if ((t & 63) == 0) part[t >> 6] = ss;
-    __syncthreads();
-    const double total = (part[0] + part[1]) + (part[2] + part[3]);
-    const float ms = (float)(total / (double)K);
+    if (kTeam == 256) {
+        if ((t & 63) == 0) part[t >> 6] = ss;
+        __syncthreads();
+        ss = (part[0] + part[1]) + (part[2] + part[3]);
+    }
+    const float ms = (float)(ss / (double)K);
     const float r = 1.0f / sqrtf(ms + eps);
 #pragma unroll
     for (int c = 0; c < MAXCH; ++c) {
-        const int k0 = c * 4096 + t * 16;
-        if (k0 < K) {   // whole teams: K is a multiple of 128
+        const int k0 = (c * kTeam + lane) * 16;
+        if (k0 < K) {   // whole groups: 8 lanes hold one, and K is a multiple of 128
             float gm[16];
             unpack16(gamma + k0, gm);
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float n = __uint_as_float(bf16_rne(v[c][i] * r) << 16);
-                v[c][i] = __uint_as_float(bf16_rne(gm[i] * n) << 16);
+            for (int i = 0; i < 16; i += 2) {
+                const uint32_t n2 = bf16_pack2(v[c][i] * r, v[c][i + 1] * r);
+                const uint32_t h2 = bf16_pack2(gm[i] * bf16_lo(n2), gm[i + 1] * bf16_hi(n2));
+                v[c][i] = bf16_lo(h2);
+                v[c][i + 1] = bf16_hi(h2);
             }
             quantize_store(v[c], q + m * K + k0, s + (m * K + k0) / kGroup, l8 == 0);
         }
@@ -163,12 +184,20 @@ hipError_t launch_rmsnorm_quant(const void* x, const void* gamma, float eps, lon
                                 float* s, hipStream_t st) {
     const uint16_t* xp = static_cast<const uint16_t*>(x);
     const uint16_t* gp = static_cast<const uint16_t*>(gamma);
-    const int chunks = (int)((K + 4095) / 4096);
-#define JET_RMS(N) hipLaunchKernelGGL(rmsnorm_quant_kernel<N>, dim3((unsigned)M), dim3(256), 0, st, xp, gp, eps, (int)K, q, s)
-    if (chunks <= 1) JET_RMS(1);
-    else if (chunks <= 2) JET_RMS(2);
-    else if (chunks <= 4) JET_RMS(4);
-    else JET_RMS(8);
+#define JET_RMS(TEAM, N, GRID) \
+    hipLaunchKernelGGL((rmsnorm_quant_kernel<TEAM, N>), dim3((unsigned)(GRID)), dim3(256), 0, st, xp, gp, eps, M, (int)K, q, s)
+    if (K <= 8192) {
+        const int chunks = (int)((K + 1023) / 1024);
+        const long grid = (M + 3) / 4;
+        if (chunks <= 1) JET_RMS(64, 1, grid);
+        else if (chunks <= 2) JET_RMS(64, 2, grid);
+        else if (chunks <= 4) JET_RMS(64, 4, grid);
+        else JET_RMS(64, 8, grid);
+    } else {
+        const int chunks = (int)((K + 4095) / 4096);
+        if (chunks <= 4) JET_RMS(256, 4, M);
+        else JET_RMS(256, 8, M);
+    }
 #undef JET_RMS
     return hipGetLastError();
 }

@@ -136,14 +136,6 @@ __device__ __forceinline__ TileList tiles_of_workgroup(int b, int n_wg, int n_ti
     return t;
 }
 
-// two floats -> two bf16 (round to nearest even) in one dword, low half first
-__device__ __forceinline__ uint32_t bf16_pack2(float lo, float hi) {
-    typedef float f32x2 __attribute__((ext_vector_type(2)));
-    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-    const f32x2 v = {lo, hi};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-}
-
 template <int SB_MODE, int WI, int WJ, int TM, int TN, int S = 2>
 __global__ __launch_bounds__(64 * WI * WJ, 512 / (64 * WI * WJ))
 void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ sa,

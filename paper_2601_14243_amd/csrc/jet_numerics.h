@@ -31,6 +31,15 @@ __device__ __forceinline__ uint32_t bf16_rne(float v) {
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
 
+// two floats -> two bf16 (round to nearest even) in one dword, low half first: one
+// hardware convert for the pair
+__device__ __forceinline__ uint32_t bf16_pack2(float lo, float hi) {
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
 // ------------------------------------------------------------- quantizer --
 
 // Scale of a group and the data needed to divide by it.

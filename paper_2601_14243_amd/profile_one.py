@@ -1,7 +1,8 @@
 """Run one entry point of libjet a few times on synthetic data, for rocprofv3.
 
     python3 paper_2601_14243_amd/profile_one.py fwd 16384 4096 4096 [iters]
-    kinds: fwd, dgrad, wgrad, quant_row, quant_dual, quant_colT, quant_weight
+    kinds: fwd, dgrad, wgrad, quant_row, quant_dual, quant_colT, quant_weight, rmsnorm_quant,
+    silu_mul_quant (for these two M, N, K mean rows, -, columns)
 
 Also launches one plain device-to-device copy of 1 GiB (torch's copy kernel): the
 HBM counters (FETCH_SIZE, WRITE_SIZE) of that launch, divided by its known size,
@@ -53,6 +54,12 @@ def main(argv):
         fn = lambda: jet.quant_act(qx["q_row"], qx["s_row"], row=False, col=True, out=qxT)
     elif kind == "quant_weight":
         fn = lambda: jet.quant_weight(w, transposed=True, out=qw)
+    elif kind == "rmsnorm_quant":
+        gamma = (1.0 + 0.1 * torch.randn((K,), generator=gen, device=dev)).to(bf)
+        fn = lambda: jet.rmsnorm_quant(x, gamma, 1e-6, out=qx)
+    elif kind == "silu_mul_quant":
+        gu = (torch.randn((M, 2 * K), generator=gen, device=dev) * 2.0).to(bf)
+        fn = lambda: jet.silu_mul_quant(gu[:, :K], gu[:, K:], out=qx)
     else:
         raise SystemExit(f"unknown kind {kind}")
     torch.cuda.synchronize()

@@ -134,3 +134,26 @@ def test_fused_producer_feeds_the_gemm_like_the_plain_quantizer(jet):
     y1 = jet.fp8_linear_fwd(fused["q_row"], fused["s_row"], qw, sw)
     y2 = jet.fp8_linear_fwd(plain["q_row"], plain["s_row"], qw, sw)
     assert torch.equal(y1.view(torch.int16), y2.view(torch.int16))
+
+
+# ------------------------------------------------------------ full sizes (8B class, M = 16384)
+
+def test_rmsnorm_quant_full_size(jet):
+    M, K = 16384, 4096
+    x = ji.activations(M, K, seed=ji.seed_for(2, 0, ji.TENSOR_X))
+    gamma = ji.norm_weight(K, seed=78)
+    want = orc.rmsnorm_quant(x, gamma, 1e-6)
+    got = jet.rmsnorm_quant(dev_bf16(x), dev_bf16(gamma.reshape(1, K)).reshape(K), 1e-6)
+    _same("q_row", host(got["q_row"]), want["q_row"])
+    _same("s_row", host(got["s_row"]), want["s_row"])
+
+
+def test_silu_mul_quant_full_size(jet):
+    """The [16384, 2 x 14336] output of a fused gate/up projection, both halves read in place."""
+    M, K = 16384, 14336
+    both = ji.mlp_intermediate(M, K, seed=ji.seed_for(2, 4, ji.TENSOR_X))
+    want = orc.silu_mul_quant(both[:, :K], both[:, K:])
+    t = dev_bf16(both)
+    got = jet.silu_mul_quant(t[:, :K], t[:, K:])
+    _same("q_row", host(got["q_row"]), want["q_row"])
+    _same("s_row", host(got["s_row"]), want["s_row"])
