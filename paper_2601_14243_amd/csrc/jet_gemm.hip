@@ -565,9 +565,21 @@ __global__ __launch_bounds__(64 * kSkWaves) void gemm_skinny_kernel(const uint8_
         }
         __syncthreads();
         if (w < 4 * RM) {                                // wave-uniform
-            for (int g = 0; g < ng; ++g) {
-                const float* src = reinterpret_cast<const float*>(pass_p + g * kGroupBytes) + cm * 320;
-                acc = chain(src[cq * 64 + l], src[256 + l], acc);
+            const float* src = reinterpret_cast<const float*>(pass_p) + cm * 320;
+            if (ng == kPass) {
+                // all LDS reads of the pass first, then the ordered chain: a loop of read, read, fma
+                // pays the LDS latency once per group (1.6 us per pass of 32 groups)
+                float pv[kPass], sv[kPass];
+#pragma unroll
+                for (int g = 0; g < kPass; ++g) {
+                    pv[g] = src[g * (kGroupBytes / 4) + cq * 64 + l];
+                    sv[g] = src[g * (kGroupBytes / 4) + 256 + l];
+                }
+#pragma unroll
+                for (int g = 0; g < kPass; ++g) acc = chain(pv[g], sv[g], acc);
+            } else {
+                for (int g = 0; g < ng; ++g)
+                    acc = chain(src[g * (kGroupBytes / 4) + cq * 64 + l], src[g * (kGroupBytes / 4) + 256 + l], acc);
             }
         }
         __syncthreads();
