@@ -627,12 +627,13 @@ struct StripCfg {
     static constexpr int kTiles = RM * CN / kWaves;             // MFMA tiles per wave
     static constexpr int kNM = (kTiles + CN - 1) / CN;          // distinct row tiles per wave
     static constexpr int kNN = kTiles < CN ? kTiles : CN;       // distinct column tiles per wave
+    static constexpr int kFetchOps = 2 * (2 * (kNM + kNN) + kNM + 1);   // LDS reads of one pair
     static_assert(RM % 2 == 0 && CN % 2 == 0 && RM * CN % kWaves == 0 && BM <= 64 && 128 % BN == 0, "");
     static_assert(kNM * kNN == kTiles, "a wave's tiles form a kNM x kNN rectangle");
-    static_assert(kWDepth >= 3 && kADepth >= 3 && (kWDepth + 1) * kWOps < 64 && (kADepth + 1) * kAOps < 64, "");
-    // Iteration p fills the buffer of chunk (2 (p + kWDepth + 1) + 1) / 16 + 1 while the reads are at
-    // group 2 p + 4 or later: the chunk that buffer held (three chunks back) must be behind every read.
-    static_assert(kSaChunk == 16 && BM / 4 <= kSaChunk && (!kSaAhead || 2 * kWDepth + 3 < kSaChunk + 6), "");
+    static_assert(kWDepth >= 4 && kADepth >= 4 && (kWDepth - 3) * kWOps < 64 && (kADepth - 3) * kAOps < 64, "");
+    // Iteration p fills the buffer of chunk (2 (p + kWDepth) + 1) / 16 + 1 while the reads are at group
+    // 2 p + 4 or later: the chunk that buffer held (three chunks back) must be behind every read.
+    static_assert(kSaChunk == 16 && BM / 4 <= kSaChunk && (!kSaAhead || 2 * kWDepth + 1 < kSaChunk + 6), "");
     static_assert(kLdsBytes <= 160 * 1024, "");
 };
 
@@ -691,18 +692,20 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const uint8_t* __restri
     // with group g it fetches 4 rows x the 16 groups of the next chunk (4 cache lines per
     // instruction instead of one per lane), so the chunk after g's is complete before its
     // first group is.
+    const bool sa_wave = w == 4;
     const float* sb_line = sb + (size_t)(j0 >> 7) * G;
-    const float* sa_line = sa + (size_t)min(i0 + l, I - 1) * G;
-    const int sa_row = l >> 4, sa_grp = l & 15;
+    const float* gs = sa_wave ? sa + (size_t)min(i0 + l, I - 1) * G : sb_line;   // one scale per lane and group
+    const int sa_grp = l & 15;
+    const int sa_off0 = (i0 + (l >> 4)) * G, sa_off_last = (I - 1) * G;          // chunk copies: this lane's row of quad 0
     const uint32_t lds_w = __builtin_amdgcn_readfirstlane(lds0 + side * kWMine * 1024);
     const uint32_t lds_a = __builtin_amdgcn_readfirstlane(lds0 + C::kWDepth * C::kWStage + side * kAMine * 1024);
     const uint32_t lds_s = __builtin_amdgcn_readfirstlane(lds0 + CN * 2048 + side * 256);
     const uint32_t lds_sa = __builtin_amdgcn_readfirstlane(lds0 + C::kSaOffset);
     // rows 4 rq .. 4 rq + 3 of the tile (past the end: the last row), groups of chunk c (past the end: the last group)
-    auto copy_sa = [&](int c, int rq) {
-        const int row = min(i0 + 4 * rq + sa_row, I - 1), grp = min(C::kSaChunk * c + sa_grp, G - 1);
-        dma4(lds_sa + (c % C::kSaBufs) * C::kSaBufBytes + rq * 256, sa + (size_t)row * G + grp);
+    auto sa_src = [&](int c, int rq) {
+        return sa + min(sa_off0 + rq * 4 * G, sa_off_last) + min(C::kSaChunk * c + sa_grp, G - 1);
     };
+    auto sa_dst = [&](int c, int rq) { return lds_sa + (c % C::kSaBufs) * C::kSaBufBytes + rq * 256; };
     // this wave's copies of pair p (groups past the end repeat the last one)
     auto issue = [&](int p) {
 #pragma unroll
@@ -712,9 +715,14 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const uint8_t* __restri
                 const uint32_t st = (p % C::kWDepth) * C::kWStage + h * C::kWGroup;
 #pragma unroll
                 for (int i = 0; i < kWMine; ++i) dma16(lds_w + st + i * 1024, baseW + (size_t)g * kGroup, off[i]);
-                if (w == 5) dma4(lds_s + st, sb_line + g);
-                else if (C::kSaAhead) copy_sa(g / C::kSaChunk + 1, (g % C::kSaChunk) % (C::BM / 4));
-                else dma4(lds_s + st, sa_line + g);
+                // (a branch between the two waves' copies: selecting source and destination per copy
+                // instead measured 10 % slower)
+                if (!C::kSaAhead || !sa_wave) {
+                    dma4(lds_s + st, gs + g);
+                } else {
+                    const int c = g / C::kSaChunk + 1, rq = (g % C::kSaChunk) % (C::BM / 4);
+                    dma4(sa_dst(c, rq), sa_src(c, rq));
+                }
             } else {
                 const uint32_t st = (p % C::kADepth) * C::kAStage + h * C::kAGroup;
 #pragma unroll
@@ -773,10 +781,15 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const uint8_t* __restri
             }
         }
     };
-    // "of my copies only those of the last depth - 2 pairs I issued may still be on their way"
-    auto wait_copies = [&]() {
-        if (w_stream) JET_WAIT_VMCNT((C::kWDepth - 2) * C::kWOps);
-        else JET_WAIT_VMCNT((C::kADepth - 2) * C::kAOps);
+    // "of my copies only those of the last n pairs I issued may still be on their way", n = depth - less
+    auto wait_copies = [&](int less) {
+        if (w_stream) {
+            if (less == 3) JET_WAIT_VMCNT((C::kWDepth - 3) * C::kWOps);
+            else JET_WAIT_VMCNT((C::kWDepth - 2) * C::kWOps);
+        } else {
+            if (less == 3) JET_WAIT_VMCNT((C::kADepth - 3) * C::kAOps);
+            else JET_WAIT_VMCNT((C::kADepth - 2) * C::kAOps);
+        }
     };
 
     // ---- L2 warm-up of this row block's activations ----
@@ -800,29 +813,25 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const uint8_t* __restri
     // in the same relative order, so the steady-state counts hold from the start
     if (C::kSaAhead && !copier) {
         // chunk 0 of the activation scales: the computing waves have nothing else to do yet
-        for (int rq = w; rq < C::BM / 4; rq += C::kWaves) copy_sa(0, rq);
+        for (int rq = w; rq < C::BM / 4; rq += C::kWaves) dma4(sa_dst(0, rq), sa_src(0, rq));
         JET_WAIT_VMCNT(0);
     }
     for (int v = 0; v < C::kWDepth; ++v)
         if (copier && (w_stream || v < C::kADepth)) issue(v);
-    if (copier) wait_copies();                       // pairs 0 and 1 landed: depth-2 later pairs outstanding
+    if (copier) wait_copies(2);                      // pairs 0 and 1 landed: depth-2 later pairs outstanding
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    // The computing waves now take pairs 0 and 1 into registers; a second barrier, and the slots of
-    // pairs 0 and 1 are free.  Iteration p (one barrier): pairs <= p+2 have landed; pairs p and p+1
-    // are in registers, pair p+2 is being fetched into registers, so the slots of pair p+1 are
-    // refilled (with pair p+1+depth): depth - 1 pairs are in flight, one slot is being read.
-    // The two kinds of wave run the same number of barriers.
+    // iteration p (one barrier): pairs <= p+2 have landed; the slots of pair p are free (its
+    // fragments are in registers).  The two kinds of wave run the same number of barriers.
+    // (Refilling the slots of pair p+1 as well -- one more pair in flight -- needs every LDS read of
+    // an iteration to return before the next barrier; measured: a few percent faster when the weights
+    // come from HBM, 10-25 % slower when they are cache-resident.)
     if (copier) {
-        const int depth = w_stream ? C::kWDepth : C::kADepth;
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        issue(depth);
         for (int p = 0; p < P; ++p) {
-            wait_copies();
+            wait_copies(3);
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
-            issue(p + depth + 1);
+            issue(p + (w_stream ? C::kWDepth : C::kADepth));
         }
         JET_WAIT_VMCNT(0);   // nothing may be in flight towards the LDS when it is released
         return;
@@ -830,16 +839,14 @@ __global__ __launch_bounds__(512) void gemm_strip_kernel(const uint8_t* __restri
     Operands op0, op1, op2;
     fetch(0, op0);
     fetch(min(1, P - 1), op1);
-    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
     auto iteration = [&](int p, const Operands& cur, Operands& nxt2) {
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         fetch(min(p + 2, P - 1), nxt2);
         compute(p, cur);
-        // my reads of pair p+2's slots are done before the next barrier lets them be overwritten
-        __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+        // my reads of pair p+1's slots are done before the next barrier lets them be overwritten
+        // (LDS reads return in order: at most the reads of pair p+2 stay outstanding)
+        __builtin_amdgcn_s_waitcnt(0xc07f | ((C::kFetchOps < 15 ? C::kFetchOps : 15) << 8));
     };
     int p = 0;
     for (; p + 2 < P; p += 3) {
