@@ -140,7 +140,7 @@ template <int SB_MODE, int WI, int WJ, int TM, int TN, int S = 2>
 __global__ __launch_bounds__(64 * WI * WJ, 512 / (64 * WI * WJ))
 void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ sa,
                       const uint8_t* __restrict__ B, const float* __restrict__ sb,
-                      uint16_t* __restrict__ out, int I, int J, int R, int tiles_i, int tiles_j) {
+                      uint16_t* __restrict__ out, int I, int ldo, int R, int tiles_i, int tiles_j) {
     using C = TileCfg<WI, WJ, TM, TN, S>;
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_ptr_t)smem;
@@ -437,8 +437,8 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
                 }
                 const int jc = j0 + (wj * TN + n + (c4 & 1)) * 16 + (c4 >> 1) * 8 + (upper ? 32 : 0);
                 const int ia = i0 + (wi * TM + m) * 16 + (r & 7);
-                if (ia < I) *reinterpret_cast<uint4*>(out + (size_t)ia * J + jc) = first;
-                if (ia + 8 < I) *reinterpret_cast<uint4*>(out + (size_t)(ia + 8) * J + jc) = second;
+                if (ia < I) *reinterpret_cast<uint4*>(out + (size_t)ia * ldo + jc) = first;
+                if (ia + 8 < I) *reinterpret_cast<uint4*>(out + (size_t)(ia + 8) * ldo + jc) = second;
             }
         }
         ++k;
@@ -892,18 +892,41 @@ using BigCfg = TileCfg<JET_BIG>;
 using SmallCfg = TileCfg<JET_SMALL>;
 using SmallDeepCfg = TileCfg<JET_SMALL_DEEP>;
 
+// out has row pitch ldo (>= J): the launches below also run on row or column ranges of a larger problem
 template <int SB_MODE>
 static hipError_t launch_tile(const uint8_t* A, const float* sa, const uint8_t* B, const float* sb,
-                              uint16_t* o, long I, long J, long R, hipStream_t st) {
+                              uint16_t* o, long I, long J, long R, long ldo, hipStream_t st) {
     // shape-only choice: the big tile when it divides J and fills the 256 CUs.  The grid
     // is persistent: at most one resident set of workgroups, each walking its tile list.
     const int cus = 256;
+    const long G = R / kGroup;
     const long big_tiles = ((I + 255) / 256) * (J / 256);
     if (J % 256 == 0 && big_tiles >= 224) {
         const int ti = (int)((I + 255) / 256), tj = (int)(J / 256);
+        // A last round that fills at most half of the CUs (896 tiles = 3.5 rounds for the 14336-wide
+        // WGrads) would cost a whole round: split those tiles off as whole tile rows or tile columns
+        // and run them as 128x128 tiles, two workgroups per CU.  An output element takes the same
+        // chain in either kernel.
+        const long tail = big_tiles % cus;
+        if (big_tiles > cus && tail > 0 && tail <= cus / 2) {
+            if (tail % tj == 0) {
+                const long i_main = (ti - tail / tj) * 256;
+                hipError_t e = launch_tile<SB_MODE>(A, sa, B, sb, o, i_main, J, R, ldo, st);
+                if (e != hipSuccess) return e;
+                return launch_tile<SB_MODE>(A + i_main * R, sa + i_main * G, B, sb, o + i_main * ldo, I - i_main, J,
+                                            R, ldo, st);
+            }
+            if (tail % ti == 0) {
+                const long j_main = (tj - tail / ti) * 256;
+                hipError_t e = launch_tile<SB_MODE>(A, sa, B, sb, o, I, j_main, R, ldo, st);
+                if (e != hipSuccess) return e;
+                const float* sb_tail = sb + (SB_MODE == kSbBlock ? (j_main / kGroup) * G : j_main * G);
+                return launch_tile<SB_MODE>(A, sa, B + j_main * R, sb_tail, o + j_main, I, J - j_main, R, ldo, st);
+            }
+        }
         const long wgs = std::min<long>((long)ti * tj, (long)cus * BigCfg::kOccupancy);
         hipLaunchKernelGGL((gemm_tile_kernel<SB_MODE, JET_BIG>), dim3((unsigned)wgs),
-                           dim3(BigCfg::kThreads), BigCfg::kLdsBytes, st, A, sa, B, sb, o, (int)I, (int)J,
+                           dim3(BigCfg::kThreads), BigCfg::kLdsBytes, st, A, sa, B, sb, o, (int)I, (int)ldo,
                            (int)R, ti, tj);
     } else {
         const int ti = (int)((I + 127) / 128), tj = (int)(J / 128);
@@ -912,13 +935,13 @@ static hipError_t launch_tile(const uint8_t* A, const float* sa, const uint8_t* 
             // that come from HBM (decode batches against cold weights) are fetched three steps ahead
             hipLaunchKernelGGL((gemm_tile_kernel<SB_MODE, JET_SMALL_DEEP>), dim3((unsigned)(ti * tj)),
                                dim3(SmallDeepCfg::kThreads), SmallDeepCfg::kLdsBytes, st, A, sa, B, sb, o, (int)I,
-                               (int)J, (int)R, ti, tj);
+                               (int)ldo, (int)R, ti, tj);
             return hipGetLastError();
         }
         const long wgs = std::min<long>((long)ti * tj, (long)cus * SmallCfg::kOccupancy);
         hipLaunchKernelGGL((gemm_tile_kernel<SB_MODE, JET_SMALL>), dim3((unsigned)wgs),
                            dim3(SmallCfg::kThreads), SmallCfg::kLdsBytes, st, A, sa, B, sb, o, (int)I,
-                           (int)J, (int)R, ti, tj);
+                           (int)ldo, (int)R, ti, tj);
     }
     return hipGetLastError();
 }
@@ -985,8 +1008,8 @@ hipError_t launch_gemm(const uint8_t* A, const float* sa, const uint8_t* B, cons
         }
         return hipGetLastError();
     }
-    if (sb_mode == kSbBlock) return launch_tile<kSbBlock>(A, sa, B, sb, o, I, J, R, st);
-    return launch_tile<kSbRow>(A, sa, B, sb, o, I, J, R, st);
+    if (sb_mode == kSbBlock) return launch_tile<kSbBlock>(A, sa, B, sb, o, I, J, R, J, st);
+    return launch_tile<kSbRow>(A, sa, B, sb, o, I, J, R, J, st);
 }
 
 }  // namespace jet

@@ -115,6 +115,42 @@ def test_wgrad_half_filled_last_tile_row(jet):
     check_gemm(host_bits(dw), ref, f"wgrad {M}x{N}x{K}")
 
 
+@pytest.mark.parametrize("M,N,K,what", [
+    (2200, 8192, 256, "rows"),      # 9 x 32 = 288 tiles of 256 x 256: the last (ragged) tile row goes to the small tile
+    (8192, 2304, 256, "columns"),   # 32 x 9 = 288 tiles: the last tile column goes to the small tile
+])
+def test_forward_with_the_last_round_split_off(jet, M, N, K, what):
+    """Tile counts just above a multiple of the CU count: the launch runs the full rounds on
+    256x256 tiles and the remaining tile row / tile column on 128x128 tiles.  Every element is
+    checked against the oracle, and rows on both sides of the seam agree with it equally often."""
+    x, w = ji.activations(M, K, 5101 + M), ji.weights(N, K, 5102 + N)
+    qa = orc.quant_act(x)
+    qw, sw = orc.quant_weight(w)
+    ref = orc.gemm(qa["q_row"], qa["s_row"], qw, sw)
+    y = host_bits(jet.fp8_linear_fwd(dev(qa["q_row"]), dev(qa["s_row"]), dev(qw), dev(sw)))
+    check_gemm(y, ref, f"fwd split {what} {M}x{N}x{K}", operands=(qa["q_row"], qa["s_row"], qw, sw, False))
+    same = (y == ref["out"])
+    if what == "rows":
+        assert abs(same[2048:].mean() - same[:2048].mean()) < 0.01
+    else:
+        assert abs(same[:, 2048:].mean() - same[:, :2048].mean()) < 0.01
+
+
+@pytest.mark.parametrize("N,K", [(2304, 8192), (8192, 2304)])
+def test_wgrad_with_the_last_round_split_off(jet, N, K):
+    """The same split for WGrad (per-row scales on both operands): by tile rows of the output
+    (N = 2304) and by tile columns (K = 2304)."""
+    M = 256
+    dy, x = ji.grads(M, N, seed=93), ji.activations(M, K, seed=94)
+    qd = orc.quant_act(dy, row=False, col=True)
+    qx = orc.quant_act(x, row=False, col=True)
+    ref = orc.gemm(qd["q_colT"], qd["s_colT"], qx["q_colT"], qx["s_colT"], sb_mode=orc.SB_ROW)
+    dw = jet.fp8_linear_wgrad(dev(qd["q_colT"]), dev(qd["s_colT"]), dev(qx["q_colT"]), dev(qx["s_colT"]))
+    assert tuple(dw.shape) == (N, K)
+    check_gemm(host_bits(dw), ref, f"wgrad split {M}x{N}x{K}",
+               operands=(qd["q_colT"], qd["s_colT"], qx["q_colT"], qx["s_colT"], True))
+
+
 def test_full_backward_from_fp8_saved_activation(jet):
     """The backward pass as the method runs it: dY quantized both ways in one pass, the
     FP8-saved X re-quantized along tokens, then DGrad and WGrad -- all on the GPU,
