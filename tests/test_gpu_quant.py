@@ -136,3 +136,44 @@ def test_same_call_twice_same_bytes(jet):
     b = jet.quant_act(x, row=True, col=True)
     for k in a:
         assert torch.equal(a[k], b[k])
+
+
+def test_hardware_convert_on_every_rounding_boundary(jet):
+    """The binary32 -> E4M3 conversion inside the kernels, probed value by value: with an FP8
+    source whose codes are 1.0 and whose per-row scales are the test values, a column group of
+    128 rows holds 127 arbitrary binary32 values v and one anchor 448, so S = 1 and the code
+    written for a row is the conversion of v itself.  Test values: for every binade from 2^-13
+    to 2^8 and each of the 16 leading 4-bit mantissa patterns (3 E4M3 bits + the rounding bit),
+    the 19 low mantissa bits at 0, 1, 2, just below / at / above the half, all ones, and 40
+    random patterns; both signs; plus zeros, the smallest subnormals and 448 itself.  Compared
+    with the oracle's encoder directly and with its quantizer on the same tensors."""
+    rng = np.random.default_rng(20240607)
+    lows = np.array([0, 1, 2, 0x3FFFF, 0x40000, 0x40001, 0x7FFFE, 0x7FFFF], np.uint32)
+    vals = []
+    for e in range(127 - 13, 127 + 9):
+        for top in range(16):
+            low = np.concatenate([lows, rng.integers(0, 1 << 19, 40, dtype=np.uint32)])
+            vals.append((np.uint32(e) << np.uint32(23)) | (np.uint32(top) << np.uint32(19)) | low)
+    u = np.concatenate(vals)
+    u = u[u <= np.float32(448.0).view(np.uint32)]
+    extra = np.array([0x00000000, 0x00000001, 0x007FFFFF, 0x00800000, 0x3A800000, 0x3A7FFFFF, 0x3A800001,
+                      np.float32(448.0).view(np.uint32)], np.uint32)
+    u = np.concatenate([u, extra])
+    u = np.concatenate([u, u | np.uint32(0x80000000)])
+    n = len(u)
+    groups = (n + 126) // 127
+    pad = groups * 127 - n
+    v = np.concatenate([u, np.zeros(pad, np.uint32)]).view(np.float32).reshape(groups, 127)
+    M, K = groups * 128, 128
+    codes = np.full((M, K), 0x38, np.uint8)                     # 1.0
+    scales = np.ones((M, 1), np.float32)
+    scales.reshape(groups, 128)[:, 1:] = v
+    codes.reshape(groups, 128, K)[:, 0, :] = 0x7E               # the anchor row of every group: 448 x 1.0
+    want = orc.quant_act(codes, scales, src=orc.SRC_FP8_ROW, row=False, col=True)
+    got = jet.quant_act(dev(codes), dev(scales), row=False, col=True)
+    gq, gs = host(got["q_colT"]), host(got["s_colT"])
+    assert np.all(gs == 1.0)
+    _cmp("q_colT", gq, want["q_colT"])
+    direct = orc.e4m3_encode(v.reshape(-1))                     # the encoder alone, value by value
+    assert np.array_equal(gq[0].reshape(groups, 128)[:, 1:].reshape(-1), direct)
+    assert np.all(gq == gq[0:1])                                # all 128 columns saw the same values
