@@ -97,8 +97,9 @@ __device__ __forceinline__ int xcd_contiguous_id(int b, int n) {
 //         (rows 0..15, same chunk) hit 16 different 16-byte bank groups: measured 6.4
 //         cycles per ds_read_b128 (160 B/clk/CU) against 16.4 for a plain row-major tile
 //   scales: wave w's 256 B = [sa rows 32w..32w+31][sb of columns 32w..32w+31]
-// Both configurations have BM = BN = 32 * waves, so every wave copies 4 A blocks,
-// 4 B blocks and one scale line per step.
+// BM = 32 * waves, so every wave copies 4 A blocks and one scale line per step, and 4 B blocks
+// (BN = 32 * waves) or 2 (BN = 16 * waves, block scales only: the 128x64 tile for batches whose
+// 128x128 tiles would occupy at most half of the CUs).
 // ------------------------------------------------------------------------
 template <int WI, int WJ, int TM, int TN, int S = 2>
 struct TileCfg {
@@ -106,13 +107,14 @@ struct TileCfg {
     static constexpr int kThreads = 64 * kWaves;
     static constexpr int BM = WI * TM * 16, BN = WJ * TN * 16;
     static constexpr int kABytes = BM * 128, kBBytes = BN * 128;
-    static constexpr int kStageBytes = kABytes + kBBytes + (BM + BN) * 4;
+    static constexpr int kBCopies = BN / (8 * kWaves);     // 1 KB blocks of the B tile per wave and step
+    static constexpr int kStageBytes = kABytes + kBBytes + kWaves * 256;   // + one 256-byte scale line per wave
     static constexpr int kStages = S;                    // LDS stages: copies run kStages - 1 steps ahead
     static constexpr int kLdsBytes = kStages * kStageBytes;
     static constexpr int kOccupancy =                    // workgroups per CU: by waves and by LDS
         (512 / kThreads) < (160 * 1024 / kLdsBytes) ? (512 / kThreads) : (160 * 1024 / kLdsBytes);
     static_assert((S & (S - 1)) == 0 && S >= 2 && kLdsBytes <= 160 * 1024, "stages");
-    static_assert(BM == 32 * kWaves && BN == 32 * kWaves, "copy schedule assumes BM = BN = 32 * waves");
+    static_assert(BM == 32 * kWaves && (BN == 32 * kWaves || BN == 16 * kWaves), "copy schedule");
     static_assert(TM % 2 == 0 && TN % 4 == 0, "fragment double buffer and 64-column stores assume even TM and TN a multiple of 4");
 };
 
@@ -173,9 +175,12 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
     };
     const uint32_t lane_row = 32 * w + (l >> 3);
     const uint32_t lane_chunk = 16 * ((l & 7) ^ (l >> 4));
-    uint32_t offB[4];                   // B rows never run past the end: fixed per-lane offsets
+    constexpr int kBC = C::kBCopies;
+    static_assert(kBC == 4 || (kBC == 2 && SB_MODE == kSbBlock), "per-column scales need 32 columns per wave");
+    uint32_t offB[kBC];                 // B rows never run past the end: fixed per-lane offsets
 #pragma unroll
-    for (int i = 0; i < 4; ++i) offB[i] = (lane_row + 8 * i) * (uint32_t)R + (lane_chunk ^ ((i & 1) * 64));
+    for (int i = 0; i < kBC; ++i)
+        offB[i] = (8 * kBC * w + (l >> 3) + 8 * i) * (uint32_t)R + (lane_chunk ^ ((i & 1) * 64));
     auto cursor_at_tile = [&](int k) {
         int i0, j0;
         tile_origin(k, i0, j0);
@@ -188,7 +193,7 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
         if (l < 32) {
             c.gs = sa + (size_t)min(i0 + 32 * w + l, I - 1) * G;
         } else if (SB_MODE == kSbBlock) {
-            c.gs = sb + (size_t)((j0 + 32 * w + (l - 32)) >> 7) * G;
+            c.gs = sb + (size_t)((j0 + min(32 * w + (l - 32), C::BN - 1)) >> 7) * G;
         } else {
             c.gs = sb + (size_t)(j0 + 32 * w + (l - 32)) * G;
         }
@@ -209,9 +214,10 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
         return n;
     };
     const uint32_t ldsw = __builtin_amdgcn_readfirstlane(lds0 + 4 * w * 1024);
+    const uint32_t ldsb = __builtin_amdgcn_readfirstlane(lds0 + C::kABytes + kBC * w * 1024);
     const uint32_t ldss = __builtin_amdgcn_readfirstlane(lds0 + C::kABytes + C::kBBytes + w * 256);
-    constexpr int kCopies = 9;
-    // copy i (0..8) of step c into the stage at LDS offset st: A blocks, B blocks, scale line
+    constexpr int kCopies = 4 + kBC + 1;
+    // copy i of step c into the stage at LDS offset st: 4 A blocks, kBC B blocks, the scale line
     auto copy_one = [&](const Cursor& c, int i, uint32_t st) {
         const uint32_t base = ldsw + st;
         if (i < 4) {
@@ -224,12 +230,13 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
                 case 2: dma16_at<2048>(base, c.pa, off); break;
                 default: dma16_at<3072>(base, c.pa, off); break;
             }
-        } else if (i < 8) {
-            switch (i) {
-                case 4: dma16_at<C::kABytes>(base, c.pb, offB[0]); break;
-                case 5: dma16_at<C::kABytes + 1024>(base, c.pb, offB[1]); break;
-                case 6: dma16_at<C::kABytes + 2048>(base, c.pb, offB[2]); break;
-                default: dma16_at<C::kABytes + 3072>(base, c.pb, offB[3]); break;
+        } else if (i < 4 + kBC) {
+            const uint32_t bbase = ldsb + st;
+            switch (i - 4) {
+                case 0: dma16_at<0>(bbase, c.pb, offB[0]); break;
+                case 1: dma16_at<1024>(bbase, c.pb, offB[1]); break;
+                case 2: dma16_at<2048>(bbase, c.pb, offB[kBC > 2 ? 2 : 0]); break;
+                default: dma16_at<3072>(bbase, c.pb, offB[kBC > 2 ? 3 : 0]); break;
             }
         } else {
             dma4(ldss + st, c.gs);
@@ -884,6 +891,7 @@ static hipError_t allow_lds(K kernel, int bytes) {
 #define JET_BIG 2, 4, 8, 4
 #define JET_SMALL 2, 2, 4, 4
 #define JET_SMALL_DEEP 2, 2, 4, 4, 4   /* four stages, one workgroup per CU: copies three steps ahead */
+#define JET_HALF 4, 1, 2, 4, 4         /* 128x64 tile, 4 waves of 32x64, four stages */
 #define JET_STRIP_SMALL 2, 2, 4, 4   /* 32-row blocks, two workgroups per CU */
 #define JET_STRIP_WIDE 4, 2, 7, 5    /* 64-row blocks */
 using StripSmall = StripCfg<JET_STRIP_SMALL>;
@@ -891,6 +899,7 @@ using StripWide = StripCfg<JET_STRIP_WIDE>;
 using BigCfg = TileCfg<JET_BIG>;
 using SmallCfg = TileCfg<JET_SMALL>;
 using SmallDeepCfg = TileCfg<JET_SMALL_DEEP>;
+using HalfCfg = TileCfg<JET_HALF>;
 
 // out has row pitch ldo (>= J): the launches below also run on row or column ranges of a larger problem
 template <int SB_MODE>
@@ -930,6 +939,13 @@ static hipError_t launch_tile(const uint8_t* A, const float* sa, const uint8_t* 
                            (int)R, ti, tj);
     } else {
         const int ti = (int)((I + 127) / 128), tj = (int)(J / 128);
+        if (SB_MODE == kSbBlock && (long)ti * tj <= cus / 2) {
+            // 128x128 tiles would leave half of the CUs idle: 128x64 tiles, one per CU
+            hipLaunchKernelGGL((gemm_tile_kernel<kSbBlock, JET_HALF>), dim3((unsigned)(ti * tj * 2)),
+                               dim3(HalfCfg::kThreads), HalfCfg::kLdsBytes, st, A, sa, B, sb, o, (int)I, (int)ldo,
+                               (int)R, ti, tj * 2);
+            return hipGetLastError();
+        }
         if ((long)ti * tj <= cus) {
             // at most one workgroup per CU anyway: spend the LDS on two more stages, so that operands
             // that come from HBM (decode batches against cold weights) are fetched three steps ahead
@@ -957,6 +973,7 @@ hipError_t launch_gemm(const uint8_t* A, const float* sa, const uint8_t* B, cons
         if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbRow, JET_SMALL>, SmallCfg::kLdsBytes);
         if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbBlock, JET_SMALL_DEEP>, SmallDeepCfg::kLdsBytes);
         if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbRow, JET_SMALL_DEEP>, SmallDeepCfg::kLdsBytes);
+        if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbBlock, JET_HALF>, HalfCfg::kLdsBytes);
         if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<6, 4, 1>, sk_lds_bytes(6, 4, 1));
         if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<3, 8, 1>, sk_lds_bytes(3, 8, 1));
         if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<1, 8, 1>, sk_lds_bytes(1, 8, 1));
