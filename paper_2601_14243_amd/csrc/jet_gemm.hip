@@ -113,7 +113,7 @@ struct TileCfg {
     static constexpr int kLdsBytes = kStages * kStageBytes;
     static constexpr int kOccupancy =                    // workgroups per CU: by waves and by LDS
         (512 / kThreads) < (160 * 1024 / kLdsBytes) ? (512 / kThreads) : (160 * 1024 / kLdsBytes);
-    static_assert((S & (S - 1)) == 0 && S >= 2 && kLdsBytes <= 160 * 1024, "stages");
+    static_assert(S >= 2 && kLdsBytes <= 160 * 1024, "stages");
     static_assert(BM == 32 * kWaves && (BN == 32 * kWaves || BN == 16 * kWaves), "copy schedule");
     static_assert(TM % 2 == 0 && TN % 4 == 0, "fragment double buffer and 64-column stores assume even TM and TN a multiple of 4");
 };
@@ -331,10 +331,11 @@ void gemm_tile_kernel(const uint8_t* __restrict__ A, const float* __restrict__ s
 
     // `cur` is the cursor of step q+S-1 at the top of step q (its first copies are already issued)
     for (int q = 0, k = 0, g = 0; q < n_steps; ++q) {
-        const int slot = q & (S - 1), nslot = (q + 1) & (S - 1);
+        const int slot = ((S & (S - 1)) == 0) ? (q & (S - 1)) : (q % S);
+        const int nslot = (slot + 1 == S) ? 0 : slot + 1, oslot = (slot == 0) ? S - 1 : slot - 1;   // steps q+1, q+S-1
         const Cursor after = cursor_after(cur);     // step q+S (all control flow of a step is here)
         const uint32_t st_this = __builtin_amdgcn_readfirstlane(slot * C::kStageBytes);
-        const uint32_t st_other = __builtin_amdgcn_readfirstlane(((q + S - 1) & (S - 1)) * C::kStageBytes);
+        const uint32_t st_other = __builtin_amdgcn_readfirstlane(oslot * C::kStageBytes);
 
         // ---- one straight-line block from here to the end of the tile loop ----
         // scales of this step: s = sa * sb, one binary32 product per (row, column scale)
@@ -891,7 +892,7 @@ static hipError_t allow_lds(K kernel, int bytes) {
 #define JET_BIG 2, 4, 8, 4
 #define JET_SMALL 2, 2, 4, 4
 #define JET_SMALL_DEEP 2, 2, 4, 4, 4   /* four stages, one workgroup per CU: copies three steps ahead */
-#define JET_HALF 4, 1, 2, 4, 4         /* 128x64 tile, 4 waves of 32x64, four stages */
+#define JET_HALF 4, 1, 2, 4, 4         /* 128x64 tile, 4 waves of 32x64, four stages (six measured the same) */
 #define JET_STRIP_SMALL 2, 2, 4, 4   /* 32-row blocks, two workgroups per CU */
 #define JET_STRIP_WIDE 4, 2, 7, 5    /* 64-row blocks */
 using StripSmall = StripCfg<JET_STRIP_SMALL>;
