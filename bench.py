@@ -192,6 +192,7 @@ def main():
     torch.cuda.empty_cache()
     if not args.no_extras:
         out["fused_producers_8B_M16384"] = fused_producers(torch, jet, M)
+        out["mismatch_probe"] = mismatch_probe(torch, jet)
         out["train_gemms_32B_M32768"] = train_gemms_32b(torch, jet)
     if not args.no_decode_sweep:
         out["decode"] = decode_sweep(torch, jet, layer)
@@ -271,6 +272,57 @@ def fused_producers(torch, jet, M):
     res["silu_mul_quant"] = {"us": round(t * 1e6, 1), "GB/s": round(by / t / 1e9, 1),
                              "row_quantizer_alone_us": round(tq * 1e6, 1)}
     return res
+
+
+def mismatch_probe(torch, jet):
+    """The property the unified flow exists for, on a synthetic stack of 8 MLP blocks (hidden 4096,
+    intermediate 14336; RMSNorm -> FP8, gate/up FProp, SiLU*up -> FP8, down FProp, residual add):
+    64 token rows pushed through as a decode-shaped batch and at seeded positions inside a
+    training-shaped batch of 4096 rows.  Reported per depth: the largest byte-level difference
+    between the two (must be zero), and, for scale, the relative distance of the FP8 stream from the
+    same stack evaluated with bf16 GEMMs (torch.matmul) -- the rollout/training gap a mixed
+    BF16-train / FP8-rollout setup would carry."""
+    dev, H, I, L, T, MB = "cuda:0", 4096, 14336, 8, 64, 4096
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(31337)
+    blocks = []
+    for _ in range(L):
+        gamma = (1.0 + 0.1 * torch.randn((H,), generator=gen, device=dev)).to(torch.bfloat16)
+        w_gu = (torch.randn((2 * I, H), generator=gen, device=dev) * 0.02).to(torch.bfloat16)
+        w_d = (torch.randn((H, I), generator=gen, device=dev) * 0.02).to(torch.bfloat16)
+        blocks.append((gamma, w_gu, w_d, jet.quant_weight(w_gu), jet.quant_weight(w_d)))
+
+    def fp8_stack(x):
+        outs = []
+        for gamma, _, _, (qgu, sgu), (qd, sd) in blocks:
+            h = jet.rmsnorm_quant(x, gamma, 1e-6)
+            gu = jet.fp8_linear_fwd(h["q_row"], h["s_row"], qgu, sgu)
+            a = jet.silu_mul_quant(gu[:, :I], gu[:, I:])
+            x = x + jet.fp8_linear_fwd(a["q_row"], a["s_row"], qd, sd)
+            outs.append(x)
+        return outs
+
+    def bf16_stack(x):
+        outs = []
+        for gamma, w_gu, w_d, _, _ in blocks:
+            xf = x.float()
+            n = (xf * torch.rsqrt(xf.pow(2).mean(-1, keepdim=True) + 1e-6)).to(torch.bfloat16) * gamma
+            gu = n @ w_gu.t()
+            a = torch.nn.functional.silu(gu[:, :I]) * gu[:, I:]
+            x = x + a @ w_d.t()
+            outs.append(x)
+        return outs
+
+    tokens = torch.randn((T, H), generator=gen, device=dev).to(torch.bfloat16)
+    batch = torch.randn((MB, H), generator=gen, device=dev).to(torch.bfloat16)
+    pos = torch.randperm(MB, generator=gen, device=dev)[:T]
+    batch[pos] = tokens
+    dec, trn, ref = fp8_stack(tokens), fp8_stack(batch), bf16_stack(tokens)
+    same = [int((d.view(torch.int16) != t[pos].view(torch.int16)).sum().item()) for d, t in zip(dec, trn)]
+    rel = [round(float(((d.float() - r.float()).norm() / r.float().norm()).item()), 5) for d, r in zip(dec, ref)]
+    return {"blocks": L, "tokens": T, "training_batch_rows": MB,
+            "differing_bf16_values_decode_vs_training_by_depth": same,
+            "fp8_vs_bf16_gemm_relative_l2_by_depth": rel}
 
 
 def train_gemms_32b(torch, jet):
