@@ -73,10 +73,11 @@ __device__ __forceinline__ int xcd_contiguous_id(int b, int n) {
 //
 // Per step the operand tiles of one group (BM + BN rows x 128 bytes) go global->LDS
 // directly as whole cache lines, swizzled so that every fragment ds_read_b128 is
-// conflict-free.  S LDS stages (two; four for the small tile when there is at most one
-// workgroup per CU); step q lives in stage q % S and is copied S - 1 steps ahead.
+// conflict-free.  S LDS stages (two; four for the 128x128 and 128x64 tiles when there is at
+// most one workgroup per CU); step q lives in stage q % S and is copied S - 1 steps ahead.
 //
-// Pipeline of one step q (t counts the wave's MFMA tiles, row m = t / TN, column n = t % TN):
+// Pipeline of one step q, written for S = 2 (t counts the wave's MFMA tiles, row m = t / TN,
+// column n = t % TN):
 //   top      : the column fragments cf[0..TN), the first row fragment and the scales of
 //              step q are already in registers (fetched during step q-1)
 //   t < last row : MFMA stream; row fragment m+1 is fetched from stage q&1 while row m runs;
@@ -89,14 +90,14 @@ __device__ __forceinline__ int xcd_contiguous_id(int b, int n) {
 // latency of the next step's first fragments hides under the last row of this step,
 // and every copy has about one whole step to land.
 //
-// LDS stage layout: [A tile BM*128][B tile BN*128][scales (BM+BN)*4]
+// LDS stage layout: [A tile BM*128][B tile BN*128][scales: 256 bytes per wave]
 //   tile: 1 KB block per 8 rows, copied by one instruction that moves 8 whole 128-byte
 //         lines (8 consecutive lanes = one line); fragment f (rows 16f..16f+15) = blocks 2f,
 //         2f+1.  Row q (0..7) of a block keeps its eight 16-byte chunks at
 //         q*128 + 16*(c ^ swz), swz = (row>>1)&7, so the 16 lanes of an MFMA fragment read
 //         (rows 0..15, same chunk) hit 16 different 16-byte bank groups: measured 6.4
 //         cycles per ds_read_b128 (160 B/clk/CU) against 16.4 for a plain row-major tile
-//   scales: wave w's 256 B = [sa rows 32w..32w+31][sb of columns 32w..32w+31]
+//   scales: wave w's 256 B = [sa rows 32w..32w+31][sb of columns 32w..32w+31, clamped to the tile]
 // BM = 32 * waves, so every wave copies 4 A blocks and one scale line per step, and 4 B blocks
 // (BN = 32 * waves) or 2 (BN = 16 * waves, block scales only: the 128x64 tile for batches whose
 // 128x128 tiles would occupy at most half of the CUs).
