@@ -31,6 +31,16 @@ def test_hand_worked_all_twos_times_all_halves():
     assert np.all(np.abs(r["acc"] - 128.0) <= 128.0 * 2.0 ** -22)
     assert np.all(r["out"] == 0x4300)               # bf16 128.0
     assert np.allclose(r["exact"], 128.0, rtol=2.0 ** -22)
+    # no cancellation: sum s |a b| = sum |s p| = the result itself, 128 products of 448^2 each
+    s = float(np.float32(qa["s_row"][0, 0]) * np.float32(sw[0, 0]))
+    assert np.all(r["sum_abs_prod"] == 128 * 448.0 ** 2 * s) and np.all(r["sum_abs"] == r["sum_abs_prod"])
+    assert np.allclose(r["sum_abs_prod"], 128.0, rtol=2.0 ** -22)
+    # alternate the sign of x: the result cancels to 0, the measure stays 128
+    x[0, 1::2] = 0xC000                             # bf16 -2.0
+    qa = orc.quant_act(x)
+    r = orc.gemm(qa["q_row"], qa["s_row"], qw, sw)
+    assert np.all(r["exact"] == 0.0) and np.all(r["sum_abs"] == 0.0)
+    assert np.all(r["sum_abs_prod"] == 128 * 448.0 ** 2 * s)
 
 
 @pytest.mark.parametrize("jlo,jhi,fp32_exact", [(-3, 4, False), (0, 2, True)])
@@ -101,6 +111,9 @@ def test_brute_force_exact_rationals_tiny(K):
                             for k in range(K))
             bound = float(sabs_elem) * (G + K // G) * 2.0 ** -24
             assert abs(float(r["acc"][i, jj]) - float(tot)) <= bound
+            # sum_g s_g sum_r |a_r b_r| (the cancellation measure of the GPU acceptance rule)
+            assert abs(float(r["sum_abs_prod"][i, jj]) - float(sabs_elem)) <= float(sabs_elem) * 1e-12
+            assert float(r["sum_abs_prod"][i, jj]) >= float(r["sum_abs"][i, jj]) * (1 - 1e-12)
 
 
 def test_three_gemms_against_fp64_dequantised_matmul():
@@ -196,7 +209,7 @@ def test_sampling_matches_full():
     full = orc.gemm(qa["q_row"], qa["s_row"], qw, sw)
     rows, cols = np.array([39, 0, 17]), np.array([255, 128, 127, 3])
     part = orc.gemm(qa["q_row"], qa["s_row"], qw, sw, rows=rows, cols=cols)
-    for k in ("acc", "out", "exact", "sum_abs"):
+    for k in ("acc", "out", "exact", "sum_abs", "sum_abs_prod"):
         assert np.array_equal(part[k], full[k][np.ix_(rows, cols)])
 
 
