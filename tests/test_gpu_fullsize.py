@@ -41,9 +41,10 @@ def _rows_bits(t: torch.Tensor, rows: np.ndarray) -> np.ndarray:
     return host_bits(t[torch.from_numpy(rows).to(t.device)])
 
 
-def _layer_case(jet, cfg, idx, layer, M, n_rows, do_fwd=True, do_dgrad=True, do_wgrad=True):
+def _layer_case(jet, cfg, idx, layer, M, n_rows, do_fwd=True, do_dgrad=True, do_wgrad=True, wgrad_rows=()):
     """One linear of a layer at training size: quantizers in full where the oracle can
-    afford it, GEMM outputs on sampled rows."""
+    afford it, GEMM outputs on sampled rows (all columns).  wgrad_rows: output rows of dW that
+    are checked besides the seeded ones (rows on both sides of a launch seam)."""
     name, N, K = layer[idx]
     x = ji.activations(M, K, ji.seed_for(cfg, idx, ji.TENSOR_X))
     w = ji.weights(N, K, ji.seed_for(cfg, idx, ji.TENSOR_W))
@@ -63,7 +64,7 @@ def _layer_case(jet, cfg, idx, layer, M, n_rows, do_fwd=True, do_dgrad=True, do_
     if do_fwd:
         y = jet.fp8_linear_fwd(gx["q_row"], gx["s_row"], gw[0], gw[1])
         ref = orc.gemm(ox["q_row"], ox["s_row"], oq, os_)
-        check_gemm(_rows_bits(y, rows), ref, f"{name} fwd M={M}")
+        check_gemm(_rows_bits(y, rows), ref, f"{name} fwd M={M}", operands=(ox["q_row"], ox["s_row"], oq, os_, False))
         del y
 
     if not (do_dgrad or do_wgrad):
@@ -76,12 +77,13 @@ def _layer_case(jet, cfg, idx, layer, M, n_rows, do_fwd=True, do_dgrad=True, do_
         assert np.array_equal(_rows_of(gdy["s_row"], rows), ody["s_row"]), f"{name}: dY scales"
         dx = jet.fp8_linear_dgrad(gdy["q_row"], gdy["s_row"], gw[2], gw[3])
         ref = orc.gemm(ody["q_row"], ody["s_row"], oqT, osT)
-        check_gemm(_rows_bits(dx, rows), ref, f"{name} dgrad M={M}")
+        check_gemm(_rows_bits(dx, rows), ref, f"{name} dgrad M={M}", operands=(ody["q_row"], ody["s_row"], oqT, osT, False))
         del dx
 
     if do_wgrad:
         # dW rows = output features n; the reduction runs over all M tokens
         nsel = ji.sample_rows(N, 6, ji.seed_for(cfg, idx, ji.TENSOR_POS) + 1)
+        nsel = np.unique(np.concatenate([nsel, np.asarray(wgrad_rows, np.int64)])).astype(np.int64)
         ody_c = orc.quant_act(np.ascontiguousarray(dy[:, nsel]), row=False, col=True)
         assert np.array_equal(_rows_of(gdy["q_colT"], nsel), ody_c["q_colT"]), f"{name}: dY^T codes"
         assert np.array_equal(_rows_of(gdy["s_colT"], nsel), ody_c["s_colT"]), f"{name}: dY^T scales"
@@ -94,7 +96,8 @@ def _layer_case(jet, cfg, idx, layer, M, n_rows, do_fwd=True, do_dgrad=True, do_
         assert np.array_equal(host(gxT["s_colT"]), oxT["s_colT"]), f"{name}: X^T scales"
         dw = jet.fp8_linear_wgrad(gdy["q_colT"], gdy["s_colT"], gxT["q_colT"], gxT["s_colT"])
         ref = orc.gemm(ody_c["q_colT"], ody_c["s_colT"], oxT["q_colT"], oxT["s_colT"], sb_mode=orc.SB_ROW)
-        check_gemm(_rows_bits(dw, nsel), ref, f"{name} wgrad M={M}")
+        check_gemm(_rows_bits(dw, nsel), ref, f"{name} wgrad M={M}",
+                   operands=(ody_c["q_colT"], ody_c["s_colT"], oxT["q_colT"], oxT["s_colT"], True))
 
 
 # ---- config 2: training step of the 8B-class layer at M = 16384 ----
@@ -107,12 +110,17 @@ def test_8b_k_proj_training_step(jet):
     _layer_case(jet, 2, 1, ji.LAYER_8B, 16384, 24)
 
 
-def test_8b_gate_proj_forward_and_dgrad(jet):
-    _layer_case(jet, 2, 4, ji.LAYER_8B, 16384, 12, do_wgrad=False)
+def test_8b_gate_proj_training_step(jet):
+    # WGrad output 14336 x 4096 = 56 x 16 tiles of 256 x 256 = 3.5 rounds of 256 workgroups: output rows
+    # from 12288 on are split off to the 128 x 128 tile kernel; rows on both sides of that seam
+    _layer_case(jet, 2, 4, ji.LAYER_8B, 16384, 12, wgrad_rows=(0, 255, 12287, 12288, 12415, 12416, 14335))
 
 
-def test_8b_down_proj_forward(jet):
-    _layer_case(jet, 2, 6, ji.LAYER_8B, 16384, 12, do_dgrad=False, do_wgrad=False)
+def test_8b_down_proj_training_step(jet):
+    # WGrad output 4096 x 14336 = 16 x 56 tiles: output columns from 12288 on are split off (the rows
+    # checked span all columns, i.e. both launches and the row pitch of the partial launch);
+    # DGrad reduces over N = 4096, output 16384 x 14336
+    _layer_case(jet, 2, 6, ji.LAYER_8B, 16384, 10, wgrad_rows=(0, 127, 128, 4095))
 
 
 # ---- config 4: 32B-class shapes ----
@@ -125,8 +133,10 @@ def test_32b_k_proj_training_step_long_rollout(jet):
     _layer_case(jet, 4, 1, ji.LAYER_32B, 32768, 16)
 
 
-def test_32b_gate_proj_forward_long_rollout(jet):
-    _layer_case(jet, 4, 4, ji.LAYER_32B, 32768, 8, do_dgrad=False, do_wgrad=False)
+def test_32b_gate_proj_training_step_long_rollout(jet):
+    # the widest matrix of the configurations: DGrad reduces over N = 27648 (216 groups), WGrad over
+    # 32768 tokens (256 groups) into a 27648 x 5120 output
+    _layer_case(jet, 4, 4, ji.LAYER_32B, 32768, 6, wgrad_rows=(0, 27647))
 
 
 def test_32b_down_proj_forward_long_rollout(jet):
@@ -148,7 +158,7 @@ def test_32b_decode(jet, idx, M):
     y = jet.fp8_linear_fwd(gx["q_row"], gx["s_row"], gq, gs)
     rows = ji.sample_rows(M, 8, 77 + M)
     ref = orc.gemm(ox["q_row"], ox["s_row"], oq, os_, rows=rows)
-    check_gemm(host_bits(y)[rows], ref, f"32B {name} decode M={M}")
+    check_gemm(host_bits(y)[rows], ref, f"32B {name} decode M={M}", operands=(ox["q_row"][rows], ox["s_row"][rows], oq, os_, False))
 
 
 # ---- config 1: rollout decode shapes of the 8B-class layer ----
@@ -168,7 +178,7 @@ def test_8b_decode(jet, idx, M):
     y = jet.fp8_linear_fwd(gx["q_row"], gx["s_row"], gq, gs)
     rows = ji.sample_rows(M, 12, 31 + M)
     ref = orc.gemm(ox["q_row"], ox["s_row"], oq, os_, rows=rows)
-    check_gemm(host_bits(y)[rows], ref, f"8B {name} decode M={M}")
+    check_gemm(host_bits(y)[rows], ref, f"8B {name} decode M={M}", operands=(ox["q_row"][rows], ox["s_row"][rows], oq, os_, False))
 
 
 # ---- config 3: unified-flow invariance sweep ----

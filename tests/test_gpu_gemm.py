@@ -26,7 +26,7 @@ def _fwd_case(jet, M, N, K, seed):
     ref = orc.gemm(qa["q_row"], qa["s_row"], qw, sw)
     y = jet.fp8_linear_fwd(dev(qa["q_row"]), dev(qa["s_row"]), dev(qw), dev(sw))
     torch.cuda.synchronize()
-    return host_bits(y), ref
+    return host_bits(y), ref, (qa["q_row"], qa["s_row"], qw, sw, False)
 
 
 def test_config0_forward_end_to_end(jet):
@@ -43,20 +43,20 @@ def test_config0_forward_end_to_end(jet):
     assert np.array_equal(host(gx["q_row"]), qa["q_row"]) and np.array_equal(host(gq), qw)
     assert np.array_equal(host(gx["s_row"]), qa["s_row"]) and np.array_equal(host(gs), sw)
     y = jet.fp8_linear_fwd(gx["q_row"], gx["s_row"], gq, gs)
-    check_gemm(host_bits(y), ref, "config0 fwd")
+    check_gemm(host_bits(y), ref, "config0 fwd", operands=(qa["q_row"], qa["s_row"], qw, sw, False))
 
 
 @pytest.mark.parametrize("M", [1, 2, 8, 15, 16, 17, 32, 100, 128, 129, 300])
 def test_forward_ragged_M(jet, M):
-    y, ref = _fwd_case(jet, M, 256, 384, seed=100 + M)
-    check_gemm(y, ref, f"fwd M={M}")
+    y, ref, ops = _fwd_case(jet, M, 256, 384, seed=100 + M)
+    check_gemm(y, ref, f"fwd M={M}", operands=ops)
 
 
 @pytest.mark.parametrize("N,K", [(128, 128), (1024, 4096), (384, 14336)])
 @pytest.mark.parametrize("M", [4, 160])
 def test_forward_shapes(jet, M, N, K):
-    y, ref = _fwd_case(jet, M, N, K, seed=7 * M + N)
-    check_gemm(y, ref, f"fwd {M}x{N}x{K}")
+    y, ref, ops = _fwd_case(jet, M, N, K, seed=7 * M + N)
+    check_gemm(y, ref, f"fwd {M}x{N}x{K}", operands=ops)
 
 
 @pytest.mark.parametrize("M,N,K", [(256, 384, 512), (5, 256, 128), (130, 128, 640)])
@@ -68,7 +68,7 @@ def test_dgrad(jet, M, N, K):
     assert ref["acc"].shape == (M, K)
     dx = jet.fp8_linear_dgrad(dev(qd["q_row"]), dev(qd["s_row"]), dev(qwT), dev(swT))
     assert tuple(dx.shape) == (M, K)
-    check_gemm(host_bits(dx), ref, f"dgrad {M}x{N}x{K}")
+    check_gemm(host_bits(dx), ref, f"dgrad {M}x{N}x{K}", operands=(qd["q_row"], qd["s_row"], qwT, swT, False))
 
 
 @pytest.mark.parametrize("M,N,K", [(256, 384, 512), (128, 128, 128), (1024, 256, 128)])
@@ -80,7 +80,8 @@ def test_wgrad(jet, M, N, K):
     assert ref["acc"].shape == (N, K)
     dw = jet.fp8_linear_wgrad(dev(qd["q_colT"]), dev(qd["s_colT"]), dev(qx["q_colT"]), dev(qx["s_colT"]))
     assert tuple(dw.shape) == (N, K)
-    check_gemm(host_bits(dw), ref, f"wgrad {M}x{N}x{K}")
+    check_gemm(host_bits(dw), ref, f"wgrad {M}x{N}x{K}",
+               operands=(qd["q_colT"], qd["s_colT"], qx["q_colT"], qx["s_colT"], True))
 
 
 def test_forward_ragged_rows_on_the_persistent_256_tile(jet):
@@ -112,7 +113,8 @@ def test_wgrad_half_filled_last_tile_row(jet):
     ref = orc.gemm(qd["q_colT"], qd["s_colT"], qx["q_colT"], qx["s_colT"], sb_mode=orc.SB_ROW)
     dw = jet.fp8_linear_wgrad(dev(qd["q_colT"]), dev(qd["s_colT"]), dev(qx["q_colT"]), dev(qx["s_colT"]))
     assert tuple(dw.shape) == (N, K)
-    check_gemm(host_bits(dw), ref, f"wgrad {M}x{N}x{K}")
+    check_gemm(host_bits(dw), ref, f"wgrad {M}x{N}x{K}",
+               operands=(qd["q_colT"], qd["s_colT"], qx["q_colT"], qx["s_colT"], True))
 
 
 @pytest.mark.parametrize("M,N,K,what", [
@@ -171,8 +173,9 @@ def test_full_backward_from_fp8_saved_activation(jet):
     dx = jet.fp8_linear_dgrad(gdy["q_row"], gdy["s_row"], gqT, gsT)
     dw = jet.fp8_linear_wgrad(gdy["q_colT"], gdy["s_colT"], gxT["q_colT"], gxT["s_colT"])
     assert np.array_equal(host(gxT["q_colT"]), oxT["q_colT"])
-    check_gemm(host_bits(dx), ref_dx, "backward dgrad")
-    check_gemm(host_bits(dw), ref_dw, "backward wgrad")
+    check_gemm(host_bits(dx), ref_dx, "backward dgrad", operands=(ody["q_row"], ody["s_row"], oqT, osT, False))
+    check_gemm(host_bits(dw), ref_dw, "backward wgrad",
+               operands=(ody["q_colT"], ody["s_colT"], oxT["q_colT"], oxT["s_colT"], True))
 
 
 def test_row_invariance_decode_vs_training_shapes(jet):
