@@ -44,7 +44,68 @@ def parse():
     ap.add_argument("--no-decode-sweep", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the 32B-class GEMM pass and the weight re-quantization timing")
+    ap.add_argument("--one", nargs=4, metavar=("KIND", "M", "N", "K"),
+                    help="profiling mode: run ONE entry point a few times on synthetic data, then one plain "
+                         "1 GiB device copy (its HBM counters calibrate FETCH_SIZE / WRITE_SIZE), and exit. "
+                         "KIND: fwd, dgrad, wgrad, quant_row, quant_dual, quant_colT, quant_weight, rmsnorm_quant, "
+                         "silu_mul_quant (for the last two M, N, K mean rows, -, columns)")
+    ap.add_argument("--iters", type=int, default=5, help="launches in --one mode")
     return ap.parse_args()
+
+
+def run_one(torch, jet, kind, M, N, K, iters):
+    """--one: a single entry point under the profiler (rocprofv3 -- python3 bench.py --one ...)."""
+    dev = "cuda:0"
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1234)
+    bf = torch.bfloat16
+    x = torch.randn((M, K), generator=gen, device=dev).to(bf)
+    w = (torch.randn((N, K), generator=gen, device=dev) * 0.02).to(bf)
+    dy = (torch.randn((M, N), generator=gen, device=dev) * 1e-3).to(bf)
+    qx = jet.quant_act(x)
+    qw = jet.quant_weight(w, transposed=True)
+    if kind == "fwd":
+        y = torch.empty((M, N), device=dev, dtype=bf)
+        fn = lambda: jet.fp8_linear_fwd(qx["q_row"], qx["s_row"], qw[0], qw[1], out=y)
+    elif kind == "dgrad":
+        qdy = jet.quant_act(dy)
+        dx = torch.empty((M, K), device=dev, dtype=bf)
+        fn = lambda: jet.fp8_linear_dgrad(qdy["q_row"], qdy["s_row"], qw[2], qw[3], out=dx)
+    elif kind == "wgrad":
+        qdy = jet.quant_act(dy, row=False, col=True)
+        qxT = jet.quant_act(qx["q_row"], qx["s_row"], row=False, col=True)
+        dw = torch.empty((N, K), device=dev, dtype=bf)
+        fn = lambda: jet.fp8_linear_wgrad(qdy["q_colT"], qdy["s_colT"], qxT["q_colT"], qxT["s_colT"], out=dw)
+    elif kind == "quant_row":
+        fn = lambda: jet.quant_act(x, out=qx)
+    elif kind == "quant_dual":
+        qdy = jet.quant_act(dy, row=True, col=True)
+        fn = lambda: jet.quant_act(dy, row=True, col=True, out=qdy)
+    elif kind == "quant_colT":
+        qxT = jet.quant_act(qx["q_row"], qx["s_row"], row=False, col=True)
+        fn = lambda: jet.quant_act(qx["q_row"], qx["s_row"], row=False, col=True, out=qxT)
+    elif kind == "quant_weight":
+        fn = lambda: jet.quant_weight(w, transposed=True, out=qw)
+    elif kind == "rmsnorm_quant":
+        gamma = (1.0 + 0.1 * torch.randn((K,), generator=gen, device=dev)).to(bf)
+        fn = lambda: jet.rmsnorm_quant(x, gamma, 1e-6, out=qx)
+    elif kind == "silu_mul_quant":
+        gu = (torch.randn((M, 2 * K), generator=gen, device=dev) * 2.0).to(bf)
+        fn = lambda: jet.silu_mul_quant(gu[:, :K], gu[:, K:], out=qx)
+    else:
+        raise SystemExit(f"unknown kind {kind}")
+    torch.cuda.synchronize()
+    for _ in range(iters):
+        fn()
+    torch.cuda.synchronize()
+    # calibration copy: 1 GiB read + 1 GiB written
+    a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    b = torch.empty_like(a)
+    a.fill_(1)
+    torch.cuda.synchronize()
+    b.copy_(a)
+    torch.cuda.synchronize()
+    print(f"bench.py --one: {kind} M={M} N={N} K={K} x{iters}, then one 1 GiB device copy")
 
 
 def make_inputs(torch, jet, M, layer):
@@ -100,6 +161,9 @@ def main():
         sys.exit(2)
     jet.lib()
     torch.cuda.set_device(0)
+    if args.one:
+        run_one(torch, jet, args.one[0], int(args.one[1]), int(args.one[2]), int(args.one[3]), args.iters)
+        return
     layer = ji.LAYER_8B
     M = M_TRAIN
     mats = make_inputs(torch, jet, M, layer)
@@ -367,6 +431,8 @@ def sustained_mfma(torch, jet, achieved_flops):
     import re
     import threading
 
+    from paper_2601_14243_amd import probe
+
     def sclk():
         # current shader clock from sysfs (the level marked '*'); no child process is started
         best = None
@@ -384,9 +450,9 @@ def sustained_mfma(torch, jet, achieved_flops):
     for name, zero in (("random", False), ("zero", True)):
         clk = []
         th = threading.Thread(target=lambda: (time.sleep(0.25), clk.append(sclk())))
-        jet.probe_mfma_rate(workgroups=1024, iters=4000, zero_data=zero, repeats=3)    # bring the clock to its steady state
+        probe.probe_mfma_rate(workgroups=1024, iters=4000, zero_data=zero, repeats=3)    # bring the clock to its steady state
         th.start()
-        r = jet.probe_mfma_rate(workgroups=1024, iters=4000, zero_data=zero, repeats=40)
+        r = probe.probe_mfma_rate(workgroups=1024, iters=4000, zero_data=zero, repeats=40)
         th.join()
         res[f"mfma_only_{name}_operands_tflops"] = round(r / 1e12, 1)
         res[f"mfma_only_{name}_operands_sclk_mhz"] = clk[0] if clk else None

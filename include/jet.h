@@ -22,7 +22,11 @@
  *   - Errors are return codes only.  All argument checks happen on the host
  *     before anything is launched; on error nothing is written.
  *   - Sizes: every dimension at most 2^30; the reduction length of a GEMM (K for
- *     FProp, N for DGrad, M for WGrad) below 2^24.  Otherwise: JET_ERR_SHAPE.
+ *     FProp, N for DGrad, M for WGrad) below 2^24; the row count of a tensor that
+ *     is quantized in 128x128 tiles (jet_quant_weight, and jet_quant_act whenever
+ *     the colT pair is requested) at most 65535 * 128.  Otherwise: JET_ERR_SHAPE.
+ *   - JET_ERR_LAUNCH reports the status of this call's own launch only: an error
+ *     left pending by the caller's earlier HIP calls is discarded first.
  *   - Inputs must be finite (NaN / Inf: no fault, result unspecified).
  *   - Same inputs give the same bytes on every call; kernel selection depends
  *     on shapes only and does not change any output bit.
@@ -49,6 +53,9 @@
 extern "C" {
 #endif
 
+/* The entry points below are the only symbols the library exports. */
+#define JET_API __attribute__((visibility("default")))
+
 typedef enum {
     JET_OK = 0,
     JET_ERR_NULL = 1,   /* a required pointer is NULL */
@@ -70,15 +77,17 @@ typedef enum {
  * 1x128 per-group quantization of activations and gradients (Sec. 4.2).
  * One pass over x emits either or both of
  *   row  : groups of 128 consecutive k of one row m
- *          q_row  u8 [M,K],  s_row  f32 [M,K/128]      needs K % 128 == 0
+ *          q_row  u8 [M,K],  s_row  f32 [M,K/128]
  *   colT : groups of 128 consecutive m of one column k, stored transposed
  *          q_colT u8 [K,M],  s_colT f32 [K,M/128]      needs M % 128 == 0
+ * K % 128 == 0 is required in every mode (the tensors of a layer are consumed by
+ * GEMMs whose reduction or output axis K is; the kernels work on 128-wide tiles).
  * (the 128x1 operand of WGrad; both at once is the fused quantization of dY
  * for DGrad and WGrad).  A pair is skipped when both its pointers are NULL;
  * giving only one pointer of a pair is JET_ERR_NULL; skipping both pairs is
  * JET_ERR_ARG.  x_scales is required for JET_SRC_FP8_ROW (else ignored).
  */
-jet_status jet_quant_act(const void* x, const float* x_scales, jet_src src,
+JET_API jet_status jet_quant_act(const void* x, const float* x_scales, jet_src src,
                          int64_t M, int64_t K,
                          uint8_t* q_row, float* s_row,
                          uint8_t* q_colT, float* s_colT,
@@ -91,7 +100,7 @@ jet_status jet_quant_act(const void* x, const float* x_scales, jet_src src,
  * is symmetric under transpose).  qT and sT are given together or both NULL.
  * Needs N % 128 == 0 and K % 128 == 0.
  */
-jet_status jet_quant_weight(const void* w, int64_t N, int64_t K,
+JET_API jet_status jet_quant_weight(const void* w, int64_t N, int64_t K,
                             uint8_t* q, float* s, uint8_t* qT, float* sT,
                             void* stream);
 
@@ -100,7 +109,7 @@ jet_status jet_quant_weight(const void* w, int64_t N, int64_t K,
  * X [M,K] and (qw,sw) = block quantization of W [N,K].  Any M >= 1 (decode and
  * training shapes alike); N % 128 == 0, K % 128 == 0.
  */
-jet_status jet_fp8_linear_fwd(const uint8_t* qx, const float* sx,
+JET_API jet_status jet_fp8_linear_fwd(const uint8_t* qx, const float* sx,
                               const uint8_t* qw, const float* sw,
                               void* y, int64_t M, int64_t N, int64_t K,
                               void* stream);
@@ -110,7 +119,7 @@ jet_status jet_fp8_linear_fwd(const uint8_t* qx, const float* sx,
  * of dY [M,N] (groups along N) and (qwT,swT) = the transposed copy written by
  * jet_quant_weight ([K,N], [K/128,N/128]).  Any M >= 1; N, K multiples of 128.
  */
-jet_status jet_fp8_linear_dgrad(const uint8_t* qdy, const float* sdy,
+JET_API jet_status jet_fp8_linear_dgrad(const uint8_t* qdy, const float* sdy,
                                 const uint8_t* qwT, const float* swT,
                                 void* dx, int64_t M, int64_t N, int64_t K,
                                 void* stream);
@@ -120,7 +129,7 @@ jet_status jet_fp8_linear_dgrad(const uint8_t* qdy, const float* sdy,
  * quantizations (qdyT,sdyT) [N,M],[N,M/128] and (qxT,sxT) [K,M],[K,M/128],
  * both grouped along the token axis.  M, N, K multiples of 128.
  */
-jet_status jet_fp8_linear_wgrad(const uint8_t* qdyT, const float* sdyT,
+JET_API jet_status jet_fp8_linear_wgrad(const uint8_t* qdyT, const float* sdyT,
                                 const uint8_t* qxT, const float* sxT,
                                 void* dw, int64_t M, int64_t N, int64_t K,
                                 void* stream);
@@ -140,7 +149,7 @@ jet_status jet_fp8_linear_wgrad(const uint8_t* qdyT, const float* sdyT,
  * K <= 32768 (a row is held in the registers of one workgroup).  A row of
  * zeros with eps == 0 has no defined result.
  */
-jet_status jet_rmsnorm_quant(const void* x, const void* gamma, float eps,
+JET_API jet_status jet_rmsnorm_quant(const void* x, const void* gamma, float eps,
                              int64_t M, int64_t K,
                              uint8_t* q_row, float* s_row, void* stream);
 
@@ -151,28 +160,15 @@ jet_status jet_rmsnorm_quant(const void* x, const void* gamma, float eps,
  * 0 (ld = K for two dense tensors, ld = 2K for the two halves of a fused
  * gate/up projection output).
  */
-jet_status jet_silu_mul_quant(const void* gate, const void* up, int64_t ld,
+JET_API jet_status jet_silu_mul_quant(const void* gate, const void* up, int64_t ld,
                               int64_t M, int64_t K,
                               uint8_t* q_row, float* s_row, void* stream);
 
-/*
- * Measurement aid for benchmarks; not a step of the layer.  Launches
- * `workgroups` workgroups of 8 waves that each issue 32 * iters FP8 16x16x128
- * matrix-core instructions on register operands (pseudo-random finite E4M3
- * bytes, or all zero if zero_data != 0) and nothing else, so that a caller can
- * time the rate the chip sustains for that instruction in its current power
- * state: flop = workgroups * 8 * 32 * iters * 65536.  out: device, f32
- * [workgroups * 8], one value per wave (its content is a checksum of no
- * meaning).  1 <= workgroups <= 65536, 1 <= iters <= 2^24.
- */
-jet_status jet_probe_mfma_rate(float* out, int32_t workgroups, int32_t iters,
-                               int32_t zero_data, void* stream);
-
 /* Text for a status code (static storage). */
-const char* jet_status_str(jet_status st);
+JET_API const char* jet_status_str(jet_status st);
 
 /* Library version: major * 10000 + minor * 100 + patch. */
-int jet_version(void);
+JET_API int jet_version(void);
 
 #ifdef __cplusplus
 }

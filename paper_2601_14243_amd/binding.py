@@ -52,8 +52,6 @@ def lib() -> ctypes.CDLL:
         L.jet_rmsnorm_quant.argtypes = [vp, vp, ctypes.c_float, i64, i64, vp, vp, vp]
         L.jet_silu_mul_quant.restype = i32
         L.jet_silu_mul_quant.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp]
-        L.jet_probe_mfma_rate.restype = i32
-        L.jet_probe_mfma_rate.argtypes = [vp, i32, i32, i32, vp]
         L.jet_status_str.restype = ctypes.c_char_p
         L.jet_status_str.argtypes = [i32]
         L.jet_version.restype = i32
@@ -62,10 +60,6 @@ def lib() -> ctypes.CDLL:
 
 
 # ---------------------------------------------------------------- raw calls
-
-def jet_probe_mfma_rate(out, workgroups, iters, zero_data, stream) -> int:
-    return int(lib().jet_probe_mfma_rate(out, int(workgroups), int(iters), int(zero_data), stream))
-
 
 def jet_version() -> int:
     return int(lib().jet_version())
@@ -197,11 +191,41 @@ def quant_weight(w: torch.Tensor, transposed: bool = False, out: tuple | None = 
     return (q, s, qT, sT) if transposed else (q, s)
 
 
+def _need_operand(q, s, rows_per_scale: int, name: str):
+    """FP8 codes [rows, R] with their scales [rows / rows_per_scale, R / 128]: the kernels read
+    exactly these extents from the raw pointers, so a wrong dtype, a strided view or a scale
+    array of another shape is refused here."""
+    _need(q, torch.uint8, name)
+    _need(s, torch.float32, name + " scales")
+    rows, R = q.shape
+    if R % GROUP or rows % rows_per_scale:
+        raise ValueError(f"{name}: shape {tuple(q.shape)} does not divide into its scale groups")
+    if tuple(s.shape) != (rows // rows_per_scale, R // GROUP):
+        raise ValueError(f"{name} scales: shape {tuple(s.shape)}, need {(rows // rows_per_scale, R // GROUP)}")
+    if s.device != q.device:
+        raise ValueError(f"{name}: codes and scales on different devices")
+
+
+def _gemm_out(out, shape, a, b, name: str) -> torch.Tensor:
+    if a.shape[1] != b.shape[1]:
+        raise ValueError(f"{name}: reduction lengths differ ({a.shape[1]} and {b.shape[1]})")
+    if a.device != b.device:
+        raise ValueError(f"{name}: operands on different devices")
+    if out is None:
+        return torch.empty(shape, dtype=torch.bfloat16, device=a.device)
+    _need(out, torch.bfloat16, name + " out")
+    if tuple(out.shape) != tuple(shape) or out.device != a.device:
+        raise ValueError(f"{name} out: shape {tuple(out.shape)} on {out.device}, need {tuple(shape)} on {a.device}")
+    return out
+
+
 def fp8_linear_fwd(qx, sx, qw, sw, out: torch.Tensor | None = None) -> torch.Tensor:
     """y bf16 [M,N] = X W^T."""
+    _need_operand(qx, sx, 1, "qx")
+    _need_operand(qw, sw, GROUP, "qw")
     M, K = qx.shape
     N = qw.shape[0]
-    y = torch.empty((M, N), dtype=torch.bfloat16, device=qx.device) if out is None else out
+    y = _gemm_out(out, (M, N), qx, qw, "fp8_linear_fwd")
     st = jet_fp8_linear_fwd(_ptr(qx), _ptr(sx), _ptr(qw), _ptr(sw), _ptr(y), M, N, K, _stream())
     if st:
         raise JetError(st, "jet_fp8_linear_fwd")
@@ -210,9 +234,11 @@ def fp8_linear_fwd(qx, sx, qw, sw, out: torch.Tensor | None = None) -> torch.Ten
 
 def fp8_linear_dgrad(qdy, sdy, qwT, swT, out: torch.Tensor | None = None) -> torch.Tensor:
     """dx bf16 [M,K] = dY W."""
+    _need_operand(qdy, sdy, 1, "qdy")
+    _need_operand(qwT, swT, GROUP, "qwT")
     M, N = qdy.shape
     K = qwT.shape[0]
-    dx = torch.empty((M, K), dtype=torch.bfloat16, device=qdy.device) if out is None else out
+    dx = _gemm_out(out, (M, K), qdy, qwT, "fp8_linear_dgrad")
     st = jet_fp8_linear_dgrad(_ptr(qdy), _ptr(sdy), _ptr(qwT), _ptr(swT), _ptr(dx), M, N, K, _stream())
     if st:
         raise JetError(st, "jet_fp8_linear_dgrad")
@@ -221,29 +247,12 @@ def fp8_linear_dgrad(qdy, sdy, qwT, swT, out: torch.Tensor | None = None) -> tor
 
 def fp8_linear_wgrad(qdyT, sdyT, qxT, sxT, out: torch.Tensor | None = None) -> torch.Tensor:
     """dw bf16 [N,K] = dY^T X."""
+    _need_operand(qdyT, sdyT, 1, "qdyT")
+    _need_operand(qxT, sxT, 1, "qxT")
     N, M = qdyT.shape
     K = qxT.shape[0]
-    dw = torch.empty((N, K), dtype=torch.bfloat16, device=qdyT.device) if out is None else out
+    dw = _gemm_out(out, (N, K), qdyT, qxT, "fp8_linear_wgrad")
     st = jet_fp8_linear_wgrad(_ptr(qdyT), _ptr(sdyT), _ptr(qxT), _ptr(sxT), _ptr(dw), M, N, K, _stream())
     if st:
         raise JetError(st, "jet_fp8_linear_wgrad")
     return dw
-
-
-def probe_mfma_rate(workgroups: int = 1024, iters: int = 2000, zero_data: bool = False, repeats: int = 5) -> float:
-    """Measurement aid: sustained rate (flop/s) of the register-resident FP8 16x16x128
-    matrix-core stream of ``jet_probe_mfma_rate`` on the current device and stream."""
-    out = torch.empty((workgroups * 8,), dtype=torch.float32, device="cuda")
-    st = jet_probe_mfma_rate(_ptr(out), workgroups, max(iters // 10, 1), zero_data, _stream())   # warm-up
-    if st:
-        raise JetError(st, "jet_probe_mfma_rate")
-    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    a.record()
-    for _ in range(repeats):
-        st = jet_probe_mfma_rate(_ptr(out), workgroups, iters, zero_data, _stream())
-        if st:
-            raise JetError(st, "jet_probe_mfma_rate")
-    b.record()
-    torch.cuda.synchronize()
-    flop = float(repeats) * workgroups * 8 * 32 * iters * 65536
-    return flop / (a.elapsed_time(b) * 1e-3)

@@ -8,6 +8,12 @@ inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) &
 
 inline jet_status after_launch(hipError_t e) { return e == hipSuccess ? JET_OK : JET_ERR_LAUNCH; }
 
+// The launchers report hipGetLastError() after their launch; an error left pending by the caller's
+// earlier HIP calls must not be mistaken for this call's, so it is discarded before launching.
+inline void discard_stale_error() { (void)hipGetLastError(); }
+
+constexpr int64_t kMaxTileRows = 65535LL * 128;   // the tile quantizers index 128-row tiles with gridDim.y
+
 // shared by the three GEMM entry points: operands (a,sa)[I,R], (b,sb)[J,R], out [I,J]
 jet_status gemm_entry(const uint8_t* a, const float* sa, const uint8_t* b, const float* sb, int sb_mode,
                       void* out, int64_t I, int64_t J, int64_t R, bool i_mult_128, void* stream) {
@@ -18,6 +24,7 @@ jet_status gemm_entry(const uint8_t* a, const float* sa, const uint8_t* b, const
     if (I > INT32_MAX / 2 || J > INT32_MAX / 2 || R >= (1 << 24)) return JET_ERR_SHAPE;
     if (misaligned(a) || misaligned(sa) || misaligned(b) || misaligned(sb) || misaligned(out))
         return JET_ERR_ALIGN;
+    discard_stale_error();
     return after_launch(jet::launch_gemm(a, sa, b, sb, sb_mode, out, I, J, R, static_cast<hipStream_t>(stream)));
 }
 
@@ -38,10 +45,12 @@ jet_status jet_quant_act(const void* x, const float* x_scales, jet_src src, int6
     if (K % 128) return JET_ERR_SHAPE;              /* row groups, FP8-source scales, 128-wide tiles */
     if (any_col && M % 128) return JET_ERR_SHAPE;
     if (M > INT32_MAX / 2 || K > INT32_MAX / 2) return JET_ERR_SHAPE;
+    if (any_col && M > kMaxTileRows) return JET_ERR_SHAPE;
     if (misaligned(x) || (src == JET_SRC_FP8_ROW && misaligned(x_scales)) ||
         (any_row && (misaligned(q_row) || misaligned(s_row))) ||
         (any_col && (misaligned(q_colT) || misaligned(s_colT))))
         return JET_ERR_ALIGN;
+    discard_stale_error();
     return after_launch(jet::launch_quant_act(x, x_scales, src, M, K, q_row, s_row, q_colT, s_colT,
                                               static_cast<hipStream_t>(stream)));
 }
@@ -51,9 +60,10 @@ jet_status jet_quant_weight(const void* w, int64_t N, int64_t K, uint8_t* q, flo
     if (!w || !q || !s) return JET_ERR_NULL;
     if ((qT == nullptr) != (sT == nullptr)) return JET_ERR_ARG;
     if (N < 1 || K < 1 || N % 128 || K % 128) return JET_ERR_SHAPE;
-    if (N > INT32_MAX / 2 || K > INT32_MAX / 2) return JET_ERR_SHAPE;
+    if (N > kMaxTileRows || K > INT32_MAX / 2) return JET_ERR_SHAPE;
     if (misaligned(w) || misaligned(q) || misaligned(s) || (qT && (misaligned(qT) || misaligned(sT))))
         return JET_ERR_ALIGN;
+    discard_stale_error();
     return after_launch(jet::launch_quant_weight(w, N, K, q, s, qT, sT, static_cast<hipStream_t>(stream)));
 }
 
@@ -78,6 +88,7 @@ jet_status jet_rmsnorm_quant(const void* x, const void* gamma, float eps, int64_
     if (!(eps >= 0.0f) || eps > 3.0e38f) return JET_ERR_ARG;   /* negative, NaN or infinite */
     if (M < 1 || K < 1 || K % 128 || K > 32768 || M > INT32_MAX / 2) return JET_ERR_SHAPE;
     if (misaligned(x) || misaligned(gamma) || misaligned(q_row) || misaligned(s_row)) return JET_ERR_ALIGN;
+    discard_stale_error();
     return after_launch(jet::launch_rmsnorm_quant(x, gamma, eps, M, K, q_row, s_row, static_cast<hipStream_t>(stream)));
 }
 
@@ -87,14 +98,8 @@ jet_status jet_silu_mul_quant(const void* gate, const void* up, int64_t ld, int6
     if (M < 1 || K < 1 || K % 128 || ld < K || ld % 8) return JET_ERR_SHAPE;
     if (M > INT32_MAX / 2 || K > INT32_MAX / 2 || ld > INT32_MAX / 2) return JET_ERR_SHAPE;
     if (misaligned(gate) || misaligned(up) || misaligned(q_row) || misaligned(s_row)) return JET_ERR_ALIGN;
+    discard_stale_error();
     return after_launch(jet::launch_silu_mul_quant(gate, up, ld, M, K, q_row, s_row, static_cast<hipStream_t>(stream)));
-}
-
-jet_status jet_probe_mfma_rate(float* out, int32_t workgroups, int32_t iters, int32_t zero_data, void* stream) {
-    if (!out) return JET_ERR_NULL;
-    if (workgroups < 1 || workgroups > 65536 || iters < 1 || iters > (1 << 24)) return JET_ERR_SHAPE;
-    if (misaligned(out)) return JET_ERR_ALIGN;
-    return after_launch(jet::launch_mfma_rate(out, workgroups, iters, zero_data != 0, static_cast<hipStream_t>(stream)));
 }
 
 const char* jet_status_str(jet_status st) {

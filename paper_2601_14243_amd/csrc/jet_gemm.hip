@@ -903,13 +903,25 @@ using SmallCfg = TileCfg<JET_SMALL>;
 using SmallDeepCfg = TileCfg<JET_SMALL_DEEP>;
 using HalfCfg = TileCfg<JET_HALF>;
 
+// compute units of the current device (256 on MI355X), asked once per process
+static int compute_units() {
+    static const int n = [] {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
+            v = 256;
+        return v;
+    }();
+    return n;
+}
+
 // out has row pitch ldo (>= J): the launches below also run on row or column ranges of a larger problem
 template <int SB_MODE>
 static hipError_t launch_tile(const uint8_t* A, const float* sa, const uint8_t* B, const float* sb,
                               uint16_t* o, long I, long J, long R, long ldo, hipStream_t st) {
     // shape-only choice: the big tile when it divides J and fills the 256 CUs.  The grid
     // is persistent: at most one resident set of workgroups, each walking its tile list.
-    const int cus = 256;
+    const int cus = compute_units();
     const long G = R / kGroup;
     const long big_tiles = ((I + 255) / 256) * (J / 256);
     if (J % 256 == 0 && big_tiles >= 224) {

@@ -27,8 +27,4 @@ hipError_t launch_rmsnorm_quant(const void* x, const void* gamma, float eps, lon
 hipError_t launch_gemm(const uint8_t* A, const float* sa, const uint8_t* B, const float* sb,
                        int sb_mode, void* out, long I, long J, long R, hipStream_t st);
 
-// Measurement aid: `workgroups` x 8 waves, each issuing 32 * iters FP8 16x16x128 matrix-core
-// instructions on register operands; writes one float per wave to out.
-hipError_t launch_mfma_rate(float* out, int workgroups, int iters, int zero_data, hipStream_t st);
-
 }  // namespace jet

@@ -1,8 +1,14 @@
-// Measurement aid (not a step of the layer): a register-resident stream of the FP8
-// matrix-core instruction that the GEMM kernels are built on, so that a benchmark can
-// report the rate the chip sustains for it at its own power state beside the published
-// peak.  No memory traffic inside the timed loop.
-#include "jet_internal.h"
+// libjet_probe.so -- a measurement aid of the benchmark, built beside libjet.so and not part
+// of its ABI: a register-resident stream of the FP8 matrix-core instruction that the GEMM kernels
+// are built on, so that a benchmark can report the rate the chip sustains for it at its own power
+// state beside the published peak.  No memory traffic inside the timed loop.
+//
+//   int jet_probe_mfma_rate(float* out, int32_t workgroups, int32_t iters, int32_t zero_data, void* stream)
+// launches `workgroups` workgroups of 8 waves that each issue 32 * iters instructions on register
+// operands (pseudo-random finite E4M3 bytes, or all zero if zero_data != 0):
+// flop = workgroups * 8 * 32 * iters * 65536.  out: device, f32 [workgroups * 8], one value per
+// wave (a checksum of no meaning).  1 <= workgroups <= 65536, 1 <= iters <= 2^24.  Returns the
+// status codes of include/jet.h (NULL 1, SHAPE 2, ALIGN 3, LAUNCH 5).
 #include "jet_numerics.h"
 
 namespace jet {
@@ -37,9 +43,15 @@ __global__ __launch_bounds__(512) void mfma_rate_kernel(float* __restrict__ out,
     if ((threadIdx.x & 63) == 0) out[blockIdx.x * 8 + (threadIdx.x >> 6)] = r;
 }
 
-hipError_t launch_mfma_rate(float* out, int workgroups, int iters, int zero_data, hipStream_t st) {
-    hipLaunchKernelGGL(mfma_rate_kernel, dim3((unsigned)workgroups), dim3(512), 0, st, out, iters, zero_data);
-    return hipGetLastError();
-}
-
 }  // namespace jet
+
+extern "C" __attribute__((visibility("default")))
+int jet_probe_mfma_rate(float* out, int32_t workgroups, int32_t iters, int32_t zero_data, void* stream) {
+    if (!out) return 1;
+    if (workgroups < 1 || workgroups > 65536 || iters < 1 || iters > (1 << 24)) return 2;
+    if (reinterpret_cast<uintptr_t>(out) & 15u) return 3;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(jet::mfma_rate_kernel, dim3((unsigned)workgroups), dim3(512), 0,
+                       static_cast<hipStream_t>(stream), out, iters, zero_data != 0);
+    return hipGetLastError() == hipSuccess ? 0 : 5;
+}

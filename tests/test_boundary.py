@@ -113,10 +113,73 @@ def test_fused_producer_argument_errors(L):
     assert b.jet_silu_mul_quant(A, A + 8, 256, 4, 128, A, A, None) == ALIGN
 
 
-def test_probe_argument_errors(L):
+def test_probe_library_is_separate_and_checks_its_arguments(L):
+    """The benchmark's matrix-core rate probe lives in its own library, not in the product ABI."""
+    from paper_2601_14243_amd import probe as p
+    assert not hasattr(L, "jet_probe_mfma_rate")
+    assert p.jet_probe_mfma_rate(None, 8, 8, 0, None) == NULL
+    assert p.jet_probe_mfma_rate(A, 0, 8, 0, None) == SHAPE
+    assert p.jet_probe_mfma_rate(A, 8, 0, 0, None) == SHAPE
+    assert p.jet_probe_mfma_rate(A, 1 << 20, 8, 0, None) == SHAPE
+    assert p.jet_probe_mfma_rate(A + 4, 8, 8, 0, None) == ALIGN
+
+
+def test_only_the_declared_entry_points_are_exported():
+    """Built with hidden visibility: the functions in the dynamic symbol table are the jet_* entry
+    points of the header and no C++ launcher (the HIP runtime's per-kernel handle objects, which
+    are data, stay visible)."""
+    import subprocess
+    from paper_2601_14243_amd import binding
+    out = subprocess.run(["nm", "-D", "--defined-only", binding._LIB_PATH], capture_output=True, text=True, check=True).stdout
+    funcs = {line.split()[-1] for line in out.splitlines() if len(line.split()) == 3 and line.split()[1] in "Tt"}
+    assert {f for f in funcs if not f.startswith("_")} == set(_declared()), funcs
+    assert not any("launch" in f for f in funcs), funcs
+
+
+def test_tile_quantizer_row_limit(L):
     from paper_2601_14243_amd import binding as b
-    assert b.jet_probe_mfma_rate(None, 8, 8, 0, None) == NULL
-    assert b.jet_probe_mfma_rate(A, 0, 8, 0, None) == SHAPE
-    assert b.jet_probe_mfma_rate(A, 8, 0, 0, None) == SHAPE
-    assert b.jet_probe_mfma_rate(A, 1 << 20, 8, 0, None) == SHAPE
-    assert b.jet_probe_mfma_rate(A + 4, 8, 8, 0, None) == ALIGN
+    too_many = 65536 * 128
+    assert b.jet_quant_weight(A, too_many, 128, A, A, None, None, None) == SHAPE
+    assert b.jet_quant_act(A, None, 0, too_many, 128, None, None, A, A, None) == SHAPE
+
+
+def test_tensor_helpers_refuse_what_the_kernels_would_read_out_of_bounds():
+    """The GEMM helpers take raw pointers from torch tensors: dtype, contiguity, scale shapes,
+    reduction lengths and a caller-supplied output are checked before the C call (no GPU needed:
+    the checks come first)."""
+    import torch
+    from paper_2601_14243_amd import binding as b
+    u8, f32, bf = torch.uint8, torch.float32, torch.bfloat16
+    M, N, K = 4, 256, 384
+    qx, sx = torch.zeros((M, K), dtype=u8), torch.ones((M, K // 128), dtype=f32)
+    qw, sw = torch.zeros((N, K), dtype=u8), torch.ones((N // 128, K // 128), dtype=f32)
+    for fn, args in ((b.fp8_linear_fwd, (qx, sx, qw, sw)), (b.fp8_linear_dgrad, (qx, sx, qw, sw)),
+                     (b.fp8_linear_wgrad, (qw, torch.ones((N, K // 128), dtype=f32), qw, torch.ones((N, K // 128), dtype=f32)))):
+        with pytest.raises(TypeError):                      # CPU tensors
+            fn(*args)
+    # the remaining checks are independent of the device: exercise them on a stand-in for is_cuda
+    class Fake(torch.Tensor):
+        @property
+        def is_cuda(self):
+            return True
+    fake = lambda t: t.as_subclass(Fake)
+    fqx, fsx, fqw, fsw = fake(qx), fake(sx), fake(qw), fake(sw)
+    with pytest.raises(TypeError):
+        b._need_operand(fake(qx.to(torch.int8)), fsx, 1, "qx")                     # dtype
+    with pytest.raises(TypeError):
+        b._need_operand(fake(torch.zeros((2 * M, K), dtype=u8)[::2]), fsx, 1, "qx")   # row-gathered, non-contiguous view
+    with pytest.raises(ValueError):
+        b._need_operand(fqx, fake(torch.ones((M, K // 128 + 1), dtype=f32)), 1, "qx")  # scale shape
+    with pytest.raises(ValueError):
+        b._need_operand(fqw, fake(torch.ones((N, K // 128), dtype=f32)), 128, "qw")    # per-row scales where blocks are due
+    with pytest.raises(ValueError):
+        b._need_operand(fake(torch.zeros((N, 200), dtype=u8)), fsw, 128, "qw")        # reduction not a multiple of 128
+    b._need_operand(fqx, fsx, 1, "qx")
+    b._need_operand(fqw, fsw, 128, "qw")
+    with pytest.raises(ValueError):
+        b._gemm_out(None, (M, N), fqx, fake(torch.zeros((N, K + 128), dtype=u8)), "fwd")   # K mismatch
+    with pytest.raises(ValueError):
+        b._gemm_out(fake(torch.zeros((M, N + 1), dtype=bf)), (M, N), fqx, fqw, "fwd")      # out shape
+    with pytest.raises(TypeError):
+        b._gemm_out(fake(torch.zeros((M, N), dtype=f32)), (M, N), fqx, fqw, "fwd")         # out dtype
+    assert b._gemm_out(fake(torch.zeros((M, N), dtype=bf)), (M, N), fqx, fqw, "fwd").shape == (M, N)

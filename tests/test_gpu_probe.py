@@ -8,7 +8,7 @@ pytestmark = pytest.mark.gpu
 
 @pytest.fixture(scope="module")
 def jet():
-    import paper_2601_14243_amd as j
+    from paper_2601_14243_amd import probe as j
     assert torch.cuda.is_available()
     j.lib()
     return j
