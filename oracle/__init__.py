@@ -74,6 +74,10 @@ def lib() -> ctypes.CDLL:
         L.orc_rmsnorm.argtypes = [vp, vp, ctypes.c_float, i64, i64, vp]
         L.orc_silu_mul.restype = i32
         L.orc_silu_mul.argtypes = [vp, vp, i64, i64, i64, vp]
+        L.orc_silu_grad.restype = ctypes.c_double
+        L.orc_silu_grad.argtypes = [ctypes.c_double]
+        L.orc_silu_mul_bwd.restype = i32
+        L.orc_silu_mul_bwd.argtypes = [vp, vp, i64, vp, i64, i64, vp, vp, i64]
         _lib = L
     return _lib
 
@@ -257,6 +261,30 @@ def silu_mul(gate, up):
     _check(lib().orc_silu_mul(gate.ctypes.data_as(ctypes.c_void_p), up.ctypes.data_as(ctypes.c_void_p),
                               ld, M, K, _p(h)))
     return h
+
+
+def silu_grad(g: float) -> float:
+    """silu'(g) in binary64."""
+    return float(lib().orc_silu_grad(float(g)))
+
+
+def silu_mul_bwd(gate, up, dh):
+    """Backward of h = bf16(bf16(silu(gate)) * up): returns (dgate, dup) as bf16 bits [M,K].
+    gate and up may be views of one [M, 2K] array (equal row strides); dh is dense [M,K]."""
+    gate, up = np.asarray(gate), np.asarray(up)
+    dh = _c(dh, np.uint16)
+    if gate.dtype != np.uint16 or up.dtype != np.uint16 or gate.shape != up.shape or dh.shape != gate.shape:
+        raise ValueError("gate, up and dh must be uint16 arrays of one shape")
+    M, K = gate.shape
+    if gate.strides != up.strides or gate.strides[1] != 2 or gate.strides[0] % 2:
+        raise ValueError("gate and up need unit column stride and a common row stride")
+    ld = gate.strides[0] // 2
+    dgu = np.empty((M, 2 * K), np.uint16)
+    dg, du = dgu[:, :K], dgu[:, K:]
+    _check(lib().orc_silu_mul_bwd(gate.ctypes.data_as(ctypes.c_void_p), up.ctypes.data_as(ctypes.c_void_p), ld,
+                                  _p(dh), M, K, dg.ctypes.data_as(ctypes.c_void_p),
+                                  du.ctypes.data_as(ctypes.c_void_p), 2 * K))
+    return dg, du
 
 
 def rmsnorm_quant(x, gamma, eps):

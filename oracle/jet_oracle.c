@@ -18,7 +18,8 @@
  * on tiny shapes, fp64 dequantise-then-matmul, transpose / permutation /
  * power-of-two metamorphic invariants; for the fused producers: closed forms
  * (one-hot rows, constant rows, scale invariance), a binary64 numpy evaluation,
- * and torch's binary64 silu over every finite bf16 input.
+ * and torch's binary64 silu over every finite bf16 input; for its backward: binary64 autograd of
+ * torch over every finite bf16 gate value, finite differences, closed forms at 0 and +-infinity.
  *
  * Build: gcc -O2 -std=c11 -fopenmp -fPIC -shared (no -ffast-math: every
  * division, multiplication and fma below must be the IEEE binary32 operation).
@@ -465,6 +466,46 @@ int orc_silu_mul(const uint16_t* gate, const uint16_t* up, int64_t ld, int64_t M
             volatile float t = a * u;
             if (!isfinite(t)) bad = 1;
             h[m * K + k] = orc_bf16_rne(t);
+        }
+    }
+    return bad ? ORC_ERR_NONFINITE : ORC_OK;
+}
+
+/* Backward of h = bf16( bf16(silu(g)) * u ) for the MLP block whose saved activations are FP8
+ * (Sec. 4.1: the tensors saved for the GEMMs of the backward pass are the FP8 ones, while the
+ * gradients that travel between operators stay BF16).  The element-wise operator between the
+ * down projection and the gate/up projections receives dh in bf16 and returns dgate and dup in
+ * bf16; the paper does not spell out its arithmetic.  Reading, bf16 module semantics as in the
+ * forward: with a = bf16(silu(g)) as the forward formed it,
+ *     dup   = bf16( dh * a )                    (the product of two bf16 values is exact in binary32)
+ *     da    = bf16( dh * u )
+ *     dgate = bf16( da * silu'(g) ),  silu'(g) = s (1 + g (1 - s)),  s = 1 / (1 + e^-g),
+ * the real value of da * silu'(g) rounded once (evaluated in binary64).
+ * gate, up: bf16 [M,K] with row stride ld; dh: bf16 [M,K] dense; dgate, dup: bf16 [M,K] with row
+ * stride ld_out (the two halves of one [M,2K] gradient tensor can be written in place). */
+double orc_silu_grad(double g) {
+    double s = 1.0 / (1.0 + exp(-g));
+    return s * (1.0 + g * (1.0 - s));
+}
+
+int orc_silu_mul_bwd(const uint16_t* gate, const uint16_t* up, int64_t ld, const uint16_t* dh,
+                     int64_t M, int64_t K, uint16_t* dgate, uint16_t* dup, int64_t ld_out) {
+    if (!gate || !up || !dh || !dgate || !dup) return ORC_ERR_NULL;
+    if (M < 1 || K < 1 || ld < K || ld_out < K) return ORC_ERR_SHAPE;
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t k = 0; k < K; ++k) {
+            float g = orc_bf16_to_f32(gate[m * ld + k]), u = orc_bf16_to_f32(up[m * ld + k]);
+            float d = orc_bf16_to_f32(dh[m * K + k]);
+            if (!isfinite(g) || !isfinite(u) || !isfinite(d)) bad = 1;
+            float a = orc_bf16_to_f32(orc_silu_bf16(gate[m * ld + k]));
+            volatile float pu = d * a;
+            volatile float pa = d * u;
+            if (!isfinite(pu) || !isfinite(pa)) bad = 1;
+            dup[m * ld_out + k] = orc_bf16_rne(pu);
+            double da = (double)orc_bf16_to_f32(orc_bf16_rne(pa));
+            dgate[m * ld_out + k] = orc_bf16_from_double(da * orc_silu_grad((double)g));
         }
     }
     return bad ? ORC_ERR_NONFINITE : ORC_OK;
