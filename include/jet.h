@@ -164,6 +164,21 @@ JET_API jet_status jet_silu_mul_quant(const void* gate, const void* up, int64_t 
                               int64_t M, int64_t K,
                               uint8_t* q_row, float* s_row, void* stream);
 
+/*
+ * Backward of the operator above, h = bf16( bf16(silu(g)) * u ), for an MLP block whose
+ * saved GEMM inputs are FP8 (Sec. 4.1: activations saved for the backward GEMMs are the FP8
+ * tensors; the gradients that travel between operators stay bf16).  With a = bf16(silu(g)):
+ *     dup   = bf16( dh * a ),   da = bf16( dh * u ),
+ *     dgate = bf16( da * silu'(g) ),  silu'(g) = s (1 + g (1 - s)),  s = 1 / (1 + e^-g),
+ * each the real value rounded once.  gate, up: bf16 [M,K], row stride ld; dh: bf16 [M,K]
+ * dense; dgate, dup: bf16 [M,K], row stride ld_out (ld_out = 2K writes the two halves of one
+ * [M,2K] gradient, ready for jet_quant_act with both output pairs).  K % 128 == 0,
+ * ld >= K, ld_out >= K, ld % 8 == 0, ld_out % 8 == 0.  Outputs must not alias inputs.
+ */
+JET_API jet_status jet_silu_mul_bwd(const void* gate, const void* up, int64_t ld, const void* dh,
+                                    int64_t M, int64_t K, void* dgate, void* dup, int64_t ld_out,
+                                    void* stream);
+
 /* Text for a status code (static storage). */
 JET_API const char* jet_status_str(jet_status st);
 

@@ -52,6 +52,8 @@ def lib() -> ctypes.CDLL:
         L.jet_rmsnorm_quant.argtypes = [vp, vp, ctypes.c_float, i64, i64, vp, vp, vp]
         L.jet_silu_mul_quant.restype = i32
         L.jet_silu_mul_quant.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp]
+        L.jet_silu_mul_bwd.restype = i32
+        L.jet_silu_mul_bwd.argtypes = [vp, vp, i64, vp, i64, i64, vp, vp, i64, vp]
         L.jet_status_str.restype = ctypes.c_char_p
         L.jet_status_str.argtypes = [i32]
         L.jet_version.restype = i32
@@ -95,6 +97,10 @@ def jet_rmsnorm_quant(x, gamma, eps, M, K, q_row, s_row, stream) -> int:
 
 def jet_silu_mul_quant(gate, up, ld, M, K, q_row, s_row, stream) -> int:
     return int(lib().jet_silu_mul_quant(gate, up, ld, M, K, q_row, s_row, stream))
+
+
+def jet_silu_mul_bwd(gate, up, ld, dh, M, K, dgate, dup, ld_out, stream) -> int:
+    return int(lib().jet_silu_mul_bwd(gate, up, ld, dh, M, K, dgate, dup, ld_out, stream))
 
 
 # ------------------------------------------------------- tensor conveniences
@@ -171,6 +177,29 @@ def silu_mul_quant(gate: torch.Tensor, up: torch.Tensor, out: dict | None = None
     if st:
         raise JetError(st, "jet_silu_mul_quant")
     return o
+
+
+def silu_mul_bwd(gate: torch.Tensor, up: torch.Tensor, dh: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """Backward of h = SiLU(gate) * up: returns dgu bf16 [M, 2K] = [dgate | dup] (one contiguous
+    tensor, the layout the fused gate/up projection's backward consumes)."""
+    for t, name in ((gate, "gate"), (up, "up")):
+        if not t.is_cuda or t.dtype != torch.bfloat16 or t.dim() != 2 or t.stride(1) != 1:
+            raise TypeError(f"{name}: need a 2-D CUDA bf16 tensor with unit column stride")
+    if gate.shape != up.shape or gate.stride(0) != up.stride(0):
+        raise TypeError("gate and up need one shape and one row stride")
+    _need(dh, torch.bfloat16, "dh")
+    M, K = gate.shape
+    if tuple(dh.shape) != (M, K):
+        raise ValueError("dh: need the shape of gate")
+    dgu = torch.empty((M, 2 * K), dtype=torch.bfloat16, device=gate.device) if out is None else out
+    _need(dgu, torch.bfloat16, "out")
+    if tuple(dgu.shape) != (M, 2 * K):
+        raise ValueError("out: need [M, 2K]")
+    st = jet_silu_mul_bwd(_ptr(gate), _ptr(up), gate.stride(0), _ptr(dh), M, K, _ptr(dgu),
+                          dgu.data_ptr() + 2 * K, 2 * K, _stream())
+    if st:
+        raise JetError(st, "jet_silu_mul_bwd")
+    return dgu
 
 
 def quant_weight(w: torch.Tensor, transposed: bool = False, out: tuple | None = None):

@@ -102,6 +102,16 @@ jet_status jet_silu_mul_quant(const void* gate, const void* up, int64_t ld, int6
     return after_launch(jet::launch_silu_mul_quant(gate, up, ld, M, K, q_row, s_row, static_cast<hipStream_t>(stream)));
 }
 
+jet_status jet_silu_mul_bwd(const void* gate, const void* up, int64_t ld, const void* dh, int64_t M, int64_t K,
+                            void* dgate, void* dup, int64_t ld_out, void* stream) {
+    if (!gate || !up || !dh || !dgate || !dup) return JET_ERR_NULL;
+    if (M < 1 || K < 1 || K % 128 || ld < K || ld % 8 || ld_out < K || ld_out % 8) return JET_ERR_SHAPE;
+    if (M > INT32_MAX / 2 || K > INT32_MAX / 2 || ld > INT32_MAX / 2 || ld_out > INT32_MAX / 2) return JET_ERR_SHAPE;
+    if (misaligned(gate) || misaligned(up) || misaligned(dh) || misaligned(dgate) || misaligned(dup)) return JET_ERR_ALIGN;
+    discard_stale_error();
+    return after_launch(jet::launch_silu_mul_bwd(gate, up, ld, dh, M, K, dgate, dup, ld_out, static_cast<hipStream_t>(stream)));
+}
+
 const char* jet_status_str(jet_status st) {
     switch (st) {
         case JET_OK: return "ok";

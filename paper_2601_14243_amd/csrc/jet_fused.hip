@@ -168,6 +168,68 @@ __global__ __launch_bounds__(256) void rmsnorm_quant_kernel(const uint16_t* __re
     }
 }
 
+// ------------------------------------------------------------------------
+// Backward of h = bf16(bf16(silu(g)) * u), the element-wise operator between the down projection
+// and the gate/up projections of an MLP block (Sec. 4.1: gradients between operators stay bf16):
+//   dup = bf16(dh * a),  da = bf16(dh * u),  dgate = bf16(da * silu'(g)),
+//   a = bf16(silu(g)) as in the forward,  silu'(g) = s (1 + g (1 - s)),  s = 1 / (1 + e^-g).
+// The two products of bf16 values are exact in binary32, so their bf16 rounding is the single
+// rounding of the real value.  dgate is the real value da * silu'(g) rounded once: the binary32
+// evaluation below carries an error bound (in ulps, growing towards the zero of silu' at
+// g = -1.2785 where 1 + g (1 - s) cancels), and whenever the result is closer than that bound to
+// a bf16 tie, or outside the range the bound holds in, binary64 decides.
+// ------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t silu_grad_mul_bf16(float g, float da) {
+    const float c_hi = 0x1.7154p+0f, c_lo = 0x1.d94aep-18f, ln2 = 0x1.62e43p-1f;
+    const float p2 = __builtin_amdgcn_exp2f(-g * c_hi);
+    const float e = __builtin_fmaf(p2, (-g * c_lo) * ln2, p2);     // e^-g, within 4 ulp
+    const float r = __builtin_amdgcn_rcpf(1.0f + e);               // s, within 5 ulp
+    const float om = e * r;                                        // 1 - s without cancellation, within 9 ulp
+    const float gom = g * om;
+    const float w = 1.0f + gom;                                    // absolute error <= 10 ulp(g om) + half an ulp of w
+    const float prod = da * (r * w);
+    // error of prod in its own ulps: <= 7 + 10 |g om| / |w|; doubled as the window around a tie
+    const float window = 16.0f + 24.0f * fabsf(gom) * __builtin_amdgcn_rcpf(fabsf(w));
+    const float dist = fabsf((float)(int)(__float_as_uint(prod) & 0xffffu) - 32768.0f);
+    const bool in_range = fabsf(g) <= 80.0f && fabsf(prod) >= 0x1p-100f;
+    if (!(dist > window) || !in_range) {
+        const double gd = (double)g;
+        const double sd = 1.0 / (1.0 + exp(-gd));
+        return bf16_from_double((double)da * (sd * (1.0 + gd * (1.0 - sd))));
+    }
+    return bf16_rne(prod);
+}
+
+__global__ __launch_bounds__(256) void silu_mul_bwd_kernel(const uint16_t* __restrict__ gate,
+                                                           const uint16_t* __restrict__ up, long ld,
+                                                           const uint16_t* __restrict__ dh, int chunks_per_row,
+                                                           long n_chunks, uint16_t* __restrict__ dgate,
+                                                           uint16_t* __restrict__ dup, long ld_out) {
+    const long stride = (long)gridDim.x * 256;
+    for (long c = (long)blockIdx.x * 256 + threadIdx.x; c < n_chunks; c += stride) {
+        const long m = c / chunks_per_row;
+        const long k = (c - m * chunks_per_row) * 8;
+        const uint4 g4 = *reinterpret_cast<const uint4*>(gate + m * ld + k);
+        const uint4 u4 = *reinterpret_cast<const uint4*>(up + m * ld + k);
+        const uint4 d4 = *reinterpret_cast<const uint4*>(dh + m * (long)chunks_per_row * 8 + k);
+        const uint32_t gw[4] = {g4.x, g4.y, g4.z, g4.w}, uw[4] = {u4.x, u4.y, u4.z, u4.w},
+                       dw[4] = {d4.x, d4.y, d4.z, d4.w};
+        uint32_t og[4], ou[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float g0 = bf16_lo(gw[i]), g1 = bf16_hi(gw[i]);
+            const float u0 = bf16_lo(uw[i]), u1 = bf16_hi(uw[i]);
+            const float d0 = bf16_lo(dw[i]), d1 = bf16_hi(dw[i]);
+            const float a0 = __uint_as_float(silu_bf16(g0) << 16), a1 = __uint_as_float(silu_bf16(g1) << 16);
+            ou[i] = bf16_pack2(d0 * a0, d1 * a1);
+            const uint32_t da2 = bf16_pack2(d0 * u0, d1 * u1);
+            og[i] = silu_grad_mul_bf16(g0, bf16_lo(da2)) | (silu_grad_mul_bf16(g1, bf16_hi(da2)) << 16);
+        }
+        *reinterpret_cast<uint4*>(dgate + m * ld_out + k) = uint4{og[0], og[1], og[2], og[3]};
+        *reinterpret_cast<uint4*>(dup + m * ld_out + k) = uint4{ou[0], ou[1], ou[2], ou[3]};
+    }
+}
+
 // ----------------------------------------------------------------- launch --
 
 hipError_t launch_silu_mul_quant(const void* gate, const void* up, long ld, long M, long K, uint8_t* q,
@@ -177,6 +239,17 @@ hipError_t launch_silu_mul_quant(const void* gate, const void* up, long ld, long
     hipLaunchKernelGGL(silu_mul_quant_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
                        static_cast<const uint16_t*>(gate), static_cast<const uint16_t*>(up), ld,
                        (int)(K / kGroup), n_groups, q, s);
+    return hipGetLastError();
+}
+
+hipError_t launch_silu_mul_bwd(const void* gate, const void* up, long ld, const void* dh, long M, long K,
+                               void* dgate, void* dup, long ld_out, hipStream_t st) {
+    const long n_chunks = M * (K / 8);
+    const long blocks = std::min<long>((n_chunks + 255) / 256, 256L * 32);
+    hipLaunchKernelGGL(silu_mul_bwd_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+                       static_cast<const uint16_t*>(gate), static_cast<const uint16_t*>(up), ld,
+                       static_cast<const uint16_t*>(dh), (int)(K / 8), n_chunks,
+                       static_cast<uint16_t*>(dgate), static_cast<uint16_t*>(dup), ld_out);
     return hipGetLastError();
 }
 

@@ -19,6 +19,9 @@ hipError_t launch_quant_weight(const void* w, long N, long K, uint8_t* q, float*
 // fused producers: h = SiLU(gate) * up or RMSNorm(x), in bf16 semantics, written as 1x128 FP8
 hipError_t launch_silu_mul_quant(const void* gate, const void* up, long ld, long M, long K, uint8_t* q,
                                  float* s, hipStream_t st);
+// element-wise backward of h = SiLU(gate) * up in bf16 semantics: dgate, dup from dh
+hipError_t launch_silu_mul_bwd(const void* gate, const void* up, long ld, const void* dh, long M, long K,
+                               void* dgate, void* dup, long ld_out, hipStream_t st);
 hipError_t launch_rmsnorm_quant(const void* x, const void* gamma, float eps, long M, long K, uint8_t* q,
                                 float* s, hipStream_t st);
 

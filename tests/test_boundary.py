@@ -25,7 +25,7 @@ def _declared():
 def test_header_symbols_are_exported(L):
     names = _declared()
     assert {"jet_quant_act", "jet_quant_weight", "jet_fp8_linear_fwd", "jet_fp8_linear_dgrad",
-            "jet_fp8_linear_wgrad", "jet_rmsnorm_quant", "jet_silu_mul_quant", "jet_status_str",
+            "jet_fp8_linear_wgrad", "jet_rmsnorm_quant", "jet_silu_mul_quant", "jet_silu_mul_bwd", "jet_status_str",
             "jet_version"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
@@ -111,6 +111,19 @@ def test_fused_producer_argument_errors(L):
     assert b.jet_silu_mul_quant(A, A, 64, 4, 128, A, A, None) == SHAPE               # ld < K
     assert b.jet_silu_mul_quant(A, A, 132, 4, 128, A, A, None) == SHAPE              # ld % 8
     assert b.jet_silu_mul_quant(A, A + 8, 256, 4, 128, A, A, None) == ALIGN
+
+
+def test_silu_mul_bwd_argument_errors(L):
+    from paper_2601_14243_amd import binding as b
+    assert b.jet_silu_mul_bwd(None, A, 128, A, 4, 128, A, A, 256, None) == NULL
+    assert b.jet_silu_mul_bwd(A, A, 128, None, 4, 128, A, A, 256, None) == NULL
+    assert b.jet_silu_mul_bwd(A, A, 128, A, 4, 128, A, None, 256, None) == NULL
+    assert b.jet_silu_mul_bwd(A, A, 128, A, 0, 128, A, A, 256, None) == SHAPE
+    assert b.jet_silu_mul_bwd(A, A, 128, A, 4, 200, A, A, 256, None) == SHAPE
+    assert b.jet_silu_mul_bwd(A, A, 64, A, 4, 128, A, A, 256, None) == SHAPE           # ld < K
+    assert b.jet_silu_mul_bwd(A, A, 128, A, 4, 128, A, A, 100, None) == SHAPE          # ld_out < K
+    assert b.jet_silu_mul_bwd(A, A, 132, A, 4, 128, A, A, 256, None) == SHAPE          # ld % 8
+    assert b.jet_silu_mul_bwd(A, A, 128, A + 2, 4, 128, A, A, 256, None) == ALIGN
 
 
 def test_probe_library_is_separate_and_checks_its_arguments(L):
