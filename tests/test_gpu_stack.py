@@ -71,3 +71,78 @@ def test_decode_and_training_shapes_agree_through_a_stack_of_blocks(jet):
         got = _forward(jet, blocks, batch)
         for depth, (g, b) in enumerate(zip(got, base)):
             assert torch.equal(g[pos].view(torch.int16), b.view(torch.int16)), f"M={M}: differs after block {depth}"
+
+
+def test_mismatch_probe_at_8b_sizes(jet):
+    """The paper's motivation (Sec. 3.3: a BF16-trained, FP8-rolled-out actor sees two different
+    forward graphs and the gap grows along the computation) on a synthetic stack of three MLP blocks
+    at the 8B-class sizes (hidden 4096, intermediate 14336):
+      1. unified flow: rows pushed through as a decode-shaped batch and at seeded positions of a
+         training-shaped batch agree in every byte at every depth;
+      2. the first block's FP8 stream is the oracle's: RMSNorm -> FP8 and SiLU*up -> FP8 bit for bit,
+         both GEMMs within the GEMM acceptance, each stage on sampled rows;
+      3. the distance between the FP8 stream and the same stack without quantization (binary32 on the
+         host, bf16 weights) is far above zero and grows with depth -- the mismatch a mixed-precision
+         setup carries and the unified flow does not."""
+    import oracle as orc
+    from jet_testlib import check_gemm, host, host_bits
+    H, I, L, T, MB = 4096, 14336, 3, 64, 4096
+    host_w = [(ji.norm_weight(H, seed=9600 + b), ji.weights(2 * I, H, seed=9610 + b), ji.weights(H, I, seed=9620 + b))
+              for b in range(L)]
+    blocks = [(dev_bf16(g.reshape(1, H)).reshape(H), jet.quant_weight(dev_bf16(wgu)), jet.quant_weight(dev_bf16(wd)))
+              for g, wgu, wd in host_w]
+    tok_bits = ji.activations(T, H, seed=9630)
+    tokens = dev_bf16(tok_bits)
+
+    def forward(x, keep=None):
+        out = []
+        for b, (gamma, (q_gu, s_gu), (q_d, s_d)) in enumerate(blocks):
+            h = jet.rmsnorm_quant(x, gamma, 1e-6)
+            gu = jet.fp8_linear_fwd(h["q_row"], h["s_row"], q_gu, s_gu)
+            a = jet.silu_mul_quant(gu[:, :I], gu[:, I:])
+            d = jet.fp8_linear_fwd(a["q_row"], a["s_row"], q_d, s_d)
+            if keep is not None and b == 0:
+                keep.update(h=h, gu=gu, a=a, d=d)
+            x = x + d
+            out.append(x)
+        return out
+
+    first = {}
+    dec = forward(tokens, first)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(9640)
+    batch = torch.randn((MB, H), generator=gen, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    pos = torch.from_numpy(ji.row_positions(T, MB, seed=9650)).to(DEV)
+    batch[pos] = tokens
+    trn = forward(batch)
+    # 1. zero differing values at every depth
+    for depth, (d, t) in enumerate(zip(dec, trn)):
+        assert torch.equal(d.view(torch.int16), t[pos].view(torch.int16)), f"decode and training rows differ after block {depth}"
+
+    # 2. block 0 against the oracle, stage by stage on sampled rows
+    rows = np.array([0, 1, 17, 40, T - 1])
+    gamma0, wgu0, wd0 = host_w[0]
+    o_h = orc.rmsnorm_quant(tok_bits[rows], gamma0, 1e-6)
+    assert np.array_equal(host(first["h"]["q_row"])[rows], o_h["q_row"]) and np.array_equal(host(first["h"]["s_row"])[rows], o_h["s_row"])
+    oq, os_ = orc.quant_weight(wgu0)
+    gu = host_bits(first["gu"])[rows]
+    check_gemm(gu, orc.gemm(o_h["q_row"], o_h["s_row"], oq, os_), "probe gate/up", operands=(o_h["q_row"], o_h["s_row"], oq, os_, False))
+    o_a = orc.silu_mul_quant(gu[:, :I], gu[:, I:])
+    assert np.array_equal(host(first["a"]["q_row"])[rows], o_a["q_row"]) and np.array_equal(host(first["a"]["s_row"])[rows], o_a["s_row"])
+    oq, os_ = orc.quant_weight(wd0)
+    check_gemm(host_bits(first["d"])[rows], orc.gemm(o_a["q_row"], o_a["s_row"], oq, os_), "probe down",
+               operands=(o_a["q_row"], o_a["s_row"], oq, os_, False))
+
+    # 3. distance from the unquantized stack, per depth
+    x = ji.bf16_bits_to_f32(tok_bits)
+    dist = []
+    for b, (gamma, wgu, wd) in enumerate(host_w):
+        g32, wgu32, wd32 = (ji.bf16_bits_to_f32(t) for t in (gamma, wgu, wd))
+        n = x * (1.0 / np.sqrt((x.astype(np.float64) ** 2).mean(axis=1, keepdims=True) + 1e-6)).astype(np.float32) * g32
+        gu32 = n @ wgu32.T
+        act = gu32[:, :I] / (1.0 + np.exp(-gu32[:, :I])) * gu32[:, I:]
+        x = x + act @ wd32.T
+        got = dec[b].float().cpu().numpy()
+        dist.append(float(np.linalg.norm(got - x) / np.linalg.norm(x)))
+    print("relative L2 distance FP8 stream vs unquantized stack by depth:", dist)
+    assert dist[0] > 1e-3 and all(b > a for a, b in zip(dist, dist[1:])), dist
