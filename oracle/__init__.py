@@ -47,6 +47,7 @@ def lib() -> ctypes.CDLL:
         L = ctypes.CDLL(_LIB)
         vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
         L.orc_num_threads.restype = i32
+        L.orc_set_num_threads.argtypes = [i32]
         L.orc_e4m3_decode.restype = ctypes.c_float
         L.orc_e4m3_decode.argtypes = [ctypes.c_uint8]
         L.orc_e4m3_encode.restype = ctypes.c_uint8
@@ -84,6 +85,10 @@ def lib() -> ctypes.CDLL:
 
 def num_threads() -> int:
     return int(lib().orc_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    lib().orc_set_num_threads(int(n))
 
 
 def _p(a):

@@ -59,6 +59,15 @@ int orc_num_threads(void) {
 #endif
 }
 
+/* Threads the row loops may use from now on (timing the oracle at one thread and at all). */
+void orc_set_num_threads(int n) {
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 /* ---------------------------------------------------------------- bf16 -- */
 
 float orc_bf16_to_f32(uint16_t h) {
