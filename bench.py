@@ -62,6 +62,8 @@ def parse():
                          "KIND: fwd, dgrad, wgrad, quant_row, quant_dual, quant_colT, quant_weight, rmsnorm_quant, "
                          "silu_mul_quant (for the last two M, N, K mean rows, -, columns)")
     ap.add_argument("--iters", type=int, default=5, help="launches in --one mode")
+    ap.add_argument("--only-decode", action="store_true",
+                    help="profiling mode: only the rollout (decode-shaped) sweep of the 8B-class layer")
     return ap.parse_args()
 
 
@@ -177,6 +179,9 @@ def main():
         run_one(torch, jet, args.one[0], int(args.one[1]), int(args.one[2]), int(args.one[3]), args.iters)
         return
     layer = ji.LAYER_8B
+    if args.only_decode:
+        print(json.dumps({"decode": decode_sweep(torch, jet, layer)}))
+        return
     M = M_TRAIN
     mats = make_inputs(torch, jet, M, layer)
     sum_nk = sum(N * K for _, N, K in layer)

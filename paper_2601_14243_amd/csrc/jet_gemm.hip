@@ -479,7 +479,12 @@ constexpr int sk_lds_bytes(int depth, int waves, int rm) {
 // reduction is very short
 // RM = 16-row tiles of the batch (1: I <= 16, 2: I <= 32); a unit then carries RM activation
 // fragments and gives RM MFMAs with the same weight fragment
-template <int kSkDepth, int kSkWaves, int RM>
+// ABLK = 8-row blocks of activations that hold a row of the batch ((I + 7) / 8): only these are
+// copied, and of the last one only the lines of existing rows -- every byte through a CU's
+// memory pipeline costs the same there whether it misses or hits, so at I = 1 the copy of 15
+// repeated rows would double the time of a strip.  The fragments of the other rows are read from
+// LDS that no copy wrote; their products land in output rows that are never stored.
+template <int kSkDepth, int kSkWaves, int RM, int ABLK = 2 * RM>
 __global__ __launch_bounds__(64 * kSkWaves) void gemm_skinny_kernel(const uint8_t* __restrict__ A,
                                                                      const float* __restrict__ sa,
                                                                      const uint8_t* __restrict__ B,
@@ -492,21 +497,24 @@ __global__ __launch_bounds__(64 * kSkWaves) void gemm_skinny_kernel(const uint8_
     constexpr int kUnit = sk_unit_bytes(RM), kGroupBytes = sk_group_bytes(RM), kPass = sk_pass(RM);
     constexpr int kSkRingBytes = kSkDepth * kUnit;
     constexpr int kSkRun = kPass / kSkWaves;                 // consecutive groups per wave per pass
-    constexpr int kCopies = 2 + 2 * RM + 1;                  // vector-memory operations per unit
+    constexpr int kCopies = 2 + ABLK + 1;                    // vector-memory operations per unit
     static_assert(kSkRun >= 1 && RM <= 2 && 4 * RM <= kSkWaves && (kSkDepth - 1) * kCopies < 64, "");
+    static_assert(ABLK >= 1 && ABLK <= 2 * RM, "");
     const int G = R / kGroup;
     const int j0 = blockIdx.x * 16;
 
     // copy offsets of this lane: block b = rows 8b..8b+7, one line per 8 lanes
-    uint32_t offW[2], offX[2 * RM];
+    uint32_t offW[2], offX[ABLK];
+    bool rowX[ABLK];                                         // this lane's row of block b exists
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
         const int row = 8 * b + (l >> 3);
         offW[b] = (uint32_t)row * (uint32_t)R + 16 * ((l & 7) ^ ((row >> 1) & 7));
     }
 #pragma unroll
-    for (int b = 0; b < 2 * RM; ++b) {
+    for (int b = 0; b < ABLK; ++b) {
         const int row = 8 * b + (l >> 3);
+        rowX[b] = row < I;
         offX[b] = (uint32_t)min(row, I - 1) * (uint32_t)R + 16 * ((l & 7) ^ ((row >> 1) & 7));
     }
     const uint8_t* baseW = B + (size_t)j0 * R;
@@ -530,8 +538,10 @@ __global__ __launch_bounds__(64 * kSkWaves) void gemm_skinny_kernel(const uint8_
         const uint32_t u = ring + (i % kSkDepth) * kUnit;
         dma16(u, baseW + (size_t)g * kGroup, offW[0]);
         dma16(u + 1024, baseW + (size_t)g * kGroup, offW[1]);
+        // (block b < ABLK always holds row 8 b < I, so every wave issues the same number of copies)
 #pragma unroll
-        for (int b = 0; b < 2 * RM; ++b) dma16(u + 2048 + b * 1024, A + (size_t)g * kGroup, offX[b]);
+        for (int b = 0; b < ABLK; ++b)
+            if (rowX[b]) dma16(u + 2048 + b * 1024, A + (size_t)g * kGroup, offX[b]);
         dma4(u + 2048 + RM * 2048, gs + g);
     };
 
@@ -988,10 +998,13 @@ hipError_t launch_gemm(const uint8_t* A, const float* sa, const uint8_t* B, cons
         if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbBlock, JET_SMALL_DEEP>, SmallDeepCfg::kLdsBytes);
         if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbRow, JET_SMALL_DEEP>, SmallDeepCfg::kLdsBytes);
         if (e == hipSuccess) e = allow_lds(gemm_tile_kernel<kSbBlock, JET_HALF>, HalfCfg::kLdsBytes);
-        if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<6, 4, 1>, sk_lds_bytes(6, 4, 1));
-        if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<3, 8, 1>, sk_lds_bytes(3, 8, 1));
-        if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<1, 8, 1>, sk_lds_bytes(1, 8, 1));
-        if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<2, 8, 2>, sk_lds_bytes(2, 8, 2));
+#define JET_SK_ATTR(D, W, RMT, AB) \
+    if (e == hipSuccess) e = allow_lds(gemm_skinny_kernel<D, W, RMT, AB>, sk_lds_bytes(D, W, RMT))
+        JET_SK_ATTR(6, 4, 1, 1); JET_SK_ATTR(6, 4, 1, 2);
+        JET_SK_ATTR(3, 8, 1, 1); JET_SK_ATTR(3, 8, 1, 2);
+        JET_SK_ATTR(1, 8, 1, 1); JET_SK_ATTR(1, 8, 1, 2);
+        JET_SK_ATTR(2, 8, 2, 3); JET_SK_ATTR(2, 8, 2, 4);
+#undef JET_SK_ATTR
         if (e == hipSuccess) e = allow_lds(gemm_strip_kernel<JET_STRIP_SMALL>, StripSmall::kLdsBytes);
         if (e == hipSuccess) e = allow_lds(gemm_strip_kernel<JET_STRIP_WIDE>, StripWide::kLdsBytes);
         attr_err = e;
@@ -1003,9 +1016,15 @@ hipError_t launch_gemm(const uint8_t* A, const float* sa, const uint8_t* B, cons
     // (17-32 rows with more strips than CUs go to the strip kernel below: measured faster)
     if ((I <= 16 || (I <= 32 && J / 16 <= 256)) && sb_mode == kSbBlock) {
         const unsigned strips = (unsigned)(J / 16);
-#define JET_SKINNY(D, W, RMT)                                                                              \
-    hipLaunchKernelGGL((gemm_skinny_kernel<D, W, RMT>), dim3(strips), dim3(64 * W), sk_lds_bytes(D, W, RMT), \
+#define JET_SKINNY_AB(D, W, RMT, AB)                                                                          \
+    hipLaunchKernelGGL((gemm_skinny_kernel<D, W, RMT, AB>), dim3(strips), dim3(64 * W), sk_lds_bytes(D, W, RMT), \
                        st, A, sa, B, sb, o, (int)I, (int)J, (int)R)
+        // copy only the 8-row activation blocks that hold a row of the batch
+#define JET_SKINNY(D, W, RMT)                                        \
+    do {                                                             \
+        if ((I + 7) / 8 < 2 * RMT) JET_SKINNY_AB(D, W, RMT, 2 * RMT - 1); \
+        else JET_SKINNY_AB(D, W, RMT, 2 * RMT);                      \
+    } while (0)
         if (I > 16) {
             JET_SKINNY(2, 8, 2);
         } else if (strips > 256) {
@@ -1016,6 +1035,7 @@ hipError_t launch_gemm(const uint8_t* A, const float* sa, const uint8_t* B, cons
             JET_SKINNY(6, 4, 1);
         }
 #undef JET_SKINNY
+#undef JET_SKINNY_AB
         return hipGetLastError();
     }
     // batches of 65-256 rows against a wide weight matrix (a hundred 128x128 tiles or more) are
