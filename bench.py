@@ -60,7 +60,7 @@ def parse():
                     help="profiling mode: run ONE entry point a few times on synthetic data, then one plain "
                          "1 GiB device copy (its HBM counters calibrate FETCH_SIZE / WRITE_SIZE), and exit. "
                          "KIND: fwd, dgrad, wgrad, quant_row, quant_dual, quant_colT, quant_weight, rmsnorm_quant, "
-                         "silu_mul_quant (for the last two M, N, K mean rows, -, columns)")
+                         "silu_mul_quant, silu_mul_bwd (for the last three M, N, K mean rows, -, columns)")
     ap.add_argument("--iters", type=int, default=5, help="launches in --one mode")
     ap.add_argument("--only-decode", action="store_true",
                     help="profiling mode: only the rollout (decode-shaped) sweep of the 8B-class layer")
@@ -106,6 +106,11 @@ def run_one(torch, jet, kind, M, N, K, iters):
     elif kind == "silu_mul_quant":
         gu = (torch.randn((M, 2 * K), generator=gen, device=dev) * 2.0).to(bf)
         fn = lambda: jet.silu_mul_quant(gu[:, :K], gu[:, K:], out=qx)
+    elif kind == "silu_mul_bwd":
+        gu = (torch.randn((M, 2 * K), generator=gen, device=dev) * 2.0).to(bf)
+        dh = (torch.randn((M, K), generator=gen, device=dev) * 1e-3).to(bf)
+        dgu = torch.empty_like(gu)
+        fn = lambda: jet.silu_mul_bwd(gu[:, :K], gu[:, K:], dh, out=dgu)
     else:
         raise SystemExit(f"unknown kind {kind}")
     torch.cuda.synchronize()
