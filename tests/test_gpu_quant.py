@@ -177,3 +177,41 @@ def test_hardware_convert_on_every_rounding_boundary(jet):
     direct = orc.e4m3_encode(v.reshape(-1))                     # the encoder alone, value by value
     assert np.array_equal(gq[0].reshape(groups, 128)[:, 1:].reshape(-1), direct)
     assert np.all(gq == gq[0:1])                                # all 128 columns saw the same values
+
+
+def test_every_pair_of_bf16_value_and_group_maximum(jet):
+    """The code of a value depends only on the value and on the largest magnitude of its group.
+    All 5.3e8 pairs (|x| <= amax) of finite bf16 magnitudes, every second one negative: each group
+    holds one amax and 127 consecutive smaller magnitudes.  The row kernel sees the groups as rows;
+    the tile kernel (dual mode) sees them as columns, and mixtures of them as rows.  Codes and scales
+    must equal the oracle's in every byte -- the divider (reciprocal, two corrections, IEEE fallback)
+    and the hardware convert are exercised on every operand pair the bf16 path can produce."""
+    per = G - 1
+    amax_bits = np.arange(1, 0x7F80, dtype=np.int64)
+    n_groups = (amax_bits + per - 1) // per
+    edges = np.searchsorted(np.cumsum(n_groups), np.arange(0, n_groups.sum(), 400_000))
+    edges = np.unique(np.concatenate([edges, [amax_bits.size]]))
+    sign = np.where(np.arange(per) % 2 == 1, 0x8000, 0).astype(np.uint16)
+    pairs = 0
+    for lo, hi in zip(edges[:-1], edges[1:]):
+        a = np.repeat(amax_bits[lo:hi], n_groups[lo:hi])                      # amax of every group
+        first = np.concatenate([np.arange(n) for n in n_groups[lo:hi]]) * per  # its first magnitude
+        vals = first[:, None] + np.arange(per)[None, :]
+        live = vals < a[:, None]
+        pairs += int(live.sum())
+        grp = np.zeros((-(-a.size // G) * G, G), np.uint16)                    # padded with all-zero groups
+        grp[:a.size, 0] = a
+        grp[:a.size, 1:] = np.where(live, vals, 0).astype(np.uint16) | sign
+        want_row = orc.quant_act(grp)
+        got = jet.quant_act(dev_bf16(grp))
+        _cmp(f"q_row, amax bits {lo + 1}..{hi}", host(got["q_row"]), want_row["q_row"])
+        _cmp(f"s_row, amax bits {lo + 1}..{hi}", host(got["s_row"]), want_row["s_row"])
+        # the same groups as the columns of [B * 128, 128] blocks
+        x = np.ascontiguousarray(grp.reshape(-1, G, G).transpose(0, 2, 1)).reshape(-1, G)
+        want = orc.quant_act(x, row=True, col=True)
+        got = jet.quant_act(dev_bf16(x), row=True, col=True)
+        for k in want:
+            _cmp(f"{k} (tile kernel), amax bits {lo + 1}..{hi}", host(got[k]), want[k])
+        # the column groups of x are the rows of grp
+        assert np.array_equal(host(got["q_colT"]).reshape(G, -1, G).transpose(1, 0, 2).reshape(-1, G), want_row["q_row"])
+    assert pairs == int((amax_bits).sum())
