@@ -33,6 +33,17 @@ PEAK_HBM_GBPS = 8000.0
 # those runs (a line "TRAFFIC_BYTES_PER_FPROP_DGRAD_LAUNCH=<bytes> KERNELS_AT_COMMIT=<hash>"); it is
 # null when the summary is missing.
 TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "bench_8B_M16384_hbm_counters.txt")
+DECODE_SUMMARY = os.path.join(ROOT, "profiles", "decode_8B_kernel_stats_and_fetch.txt")
+
+
+def profiled_decode_traffic():
+    """HBM reads of the largest decode launch (fused gate+up at M = 1), from the committed summary."""
+    import re
+    try:
+        m = re.search(r"READ_BYTES_FUSED_GATE_UP_M1_LAUNCH=(\d+)\s+KERNELS_AT_COMMIT=(\w+)", open(DECODE_SUMMARY).read())
+    except OSError:
+        return None, None
+    return (int(m.group(1)), m.group(2)) if m else (None, None)
 
 
 def profiled_traffic():
@@ -293,6 +304,12 @@ def main():
                                   "achieved": d1["fused_GB/s"], "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                                   "frac": d1["fused_frac_hbm"], "seven_separate_calls_frac": d1["frac_hbm"],
                                   "traffic": None}
+        rd, at = profiled_decode_traffic()
+        if rd is not None:
+            # per launch of the largest call of the layer (the per-layer figure above spans four launches)
+            out["roofline_decode"]["traffic_fused_gate_up_launch"] = {
+                "bytes_read": rd, "weight_bytes": 2 * 14336 * 4096, "profiled_at_commit": at,
+                "source": "rocprofv3 FETCH_SIZE, profiles/decode_8B_kernel_stats_and_fetch.txt"}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
         out["cpu_baseline"]["parity_config0"] = parity_config0(torch, jet)
