@@ -59,6 +59,22 @@ def test_forward_shapes(jet, M, N, K):
     check_gemm(y, ref, f"fwd {M}x{N}x{K}", operands=ops)
 
 
+@pytest.mark.parametrize("M,N,K,kernel", [
+    (20, 2048, 640, "skinny kernel, two row tiles, the second one 4 rows: three activation blocks copied"),
+    (27, 2048, 640, "skinny kernel, two row tiles, the second one 11 rows: four activation blocks copied"),
+    (27, 4608, 384, "strip kernel, one 32-row block (17-32 rows against more than 256 strips of 16 columns)"),
+    (50, 4096, 640, "strip kernel, 32-row blocks, second block 18 rows, odd number of groups"),
+    (200, 4352, 640, "strip kernel, 64-row blocks, last block holds 8 rows, odd number of groups"),
+    (100, 14336, 256, "tile kernel on 128 x 64 tiles (112 tiles of 128 x 128 would leave half of the CUs idle), ragged rows"),
+    (200, 14336, 384, "tile kernel on 128 x 128 tiles, four stages (224 tiles), ragged second tile row"),
+])
+def test_forward_ragged_rows_in_every_decode_kernel(jet, M, N, K, kernel):
+    """The launch rules of the decode path by shape, each with a row count that leaves its last
+    row block partly empty."""
+    y, ref, ops = _fwd_case(jet, M, N, K, seed=31 * M + N)
+    check_gemm(y, ref, f"fwd {M}x{N}x{K}: {kernel}", operands=ops)
+
+
 @pytest.mark.parametrize("M,N,K", [(256, 384, 512), (5, 256, 128), (130, 128, 640)])
 def test_dgrad(jet, M, N, K):
     dy, w = ji.grads(M, N, seed=M + 1), ji.weights(N, K, seed=M + 2)
