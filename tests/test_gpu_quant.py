@@ -179,6 +179,54 @@ def test_hardware_convert_on_every_rounding_boundary(jet):
     assert np.all(gq == gq[0:1])                                # all 128 columns saw the same values
 
 
+def test_hardware_convert_on_every_binary32_value_up_to_448(jet):
+    """The same probe, exhaustively: every binary32 value v with 2^-11 <= |v| <= 448 (all 2^23
+    mantissas, both signs, 20 binades: 3.3e8 values) is converted by the kernel and compared with
+    the oracle's encoder.  A row's scale runs over all sign and mantissa patterns of one binade;
+    the columns of that row hold the E4M3 codes of the powers of two 2^-9 .. 2^8, so that the
+    kernel's one multiply decode(code) * scale produces the same mantissa in 18 binades, exactly;
+    a second pass with the scales divided by 4 reaches 2^-10 and 2^-11 (below, everything rounds
+    to zero; the probe above samples that range).  Row 0 of every 128 rows is the anchor 448."""
+    exps = np.arange(-9, 9)
+    pow_codes = np.array([(1 << (e + 9)) if e < -6 else ((e + 7) << 3) for e in exps], np.uint8)
+    assert np.array_equal(orc.e4m3_decode(pow_codes), np.ldexp(np.float32(1), exps))
+    col_of = np.arange(G) % len(exps)                            # column k holds 2^exps[k % 18]
+    chunk = 1 << 21
+    total = 0
+    for scale_shift, cols in ((0, range(len(exps))), (-2, (0, 1))):
+        for c0 in range(0, 1 << 24, chunk):
+            pat = np.arange(c0, c0 + chunk, dtype=np.uint32)
+            sbits = ((pat >> np.uint32(23)) << np.uint32(31)) | np.uint32((127 + scale_shift) << 23) | (pat & np.uint32(0x7FFFFF))
+            sv = sbits.view(np.float32)
+            groups = -(-chunk // 127)
+            v = np.concatenate([sv, np.zeros(groups * 127 - chunk, np.float32)]).reshape(groups, 127)
+            M = groups * 128
+            scales = np.ones((groups, 128), np.float32)
+            scales[:, 1:] = v
+            codes = np.empty((groups, 128, G), np.uint8)
+            codes[:] = pow_codes[col_of]
+            # 2^8 * |s| must stay at or below the anchor: rows with |s| > 1.75 hold a zero in those columns
+            big = np.abs(scales) * np.float32(2.0 ** -scale_shift) > np.float32(1.75)
+            codes[np.ix_(*map(np.arange, big.shape), np.flatnonzero(exps[col_of] == 8))] = np.where(
+                big[:, :, None], 0, pow_codes[-1]).astype(np.uint8)
+            codes[:, 0, :] = 0x7E
+            got = jet.quant_act(dev(codes.reshape(M, G)), dev(scales.reshape(M, 1)), row=False, col=True)
+            gq, gs = host(got["q_colT"]), host(got["s_colT"])
+            assert np.all(gs == 1.0)
+            for k in cols:
+                x = v * np.ldexp(np.float32(1), int(exps[k]))
+                if exps[k] == 8:
+                    x = np.where(np.abs(x) > 448, np.float32(0) * v, x)     # decode(0) * s keeps the sign of s
+                want = orc.e4m3_encode(x.reshape(-1))
+                have = gq[k].reshape(groups, 128)[:, 1:].reshape(-1)
+                bad = np.flatnonzero(have != want)
+                assert bad.size == 0, (f"2^{exps[k] + scale_shift} binade: {bad.size} values differ, first "
+                                       f"{x.reshape(-1)[bad[0]]!r}: got {have[bad[0]]:#x} want {want[bad[0]]:#x}")
+                total += chunk
+            assert all(np.array_equal(gq[k], gq[k % len(exps)]) for k in range(len(exps), G))
+    assert total == 20 * (1 << 24)
+
+
 def test_every_pair_of_bf16_value_and_group_maximum(jet):
     """The code of a value depends only on the value and on the largest magnitude of its group.
     All 5.3e8 pairs (|x| <= amax) of finite bf16 magnitudes, every second one negative: each group
