@@ -210,7 +210,9 @@ def main():
     def ev():
         return torch.cuda.Event(enable_timing=True)
 
-    def timed(store, work, fn):
+    per_matrix = {}    # (matrix, GEMM kind) -> [(start, end)]
+
+    def timed(store, work, fn, tag=None):
         if store is None:
             fn()
             return
@@ -219,6 +221,8 @@ def main():
         fn()
         b.record()
         store.append((a, b, work))
+        if tag is not None:
+            per_matrix.setdefault(tag, []).append((a, b))
 
     def step(record):
         ge = gemm_events if record else None
@@ -229,11 +233,11 @@ def main():
             fl = 2 * M * N * K
             timed(qe, N * K * 4.0, lambda: jet.quant_weight(m["w"], transposed=True, out=m["qw"]))
             timed(qe, M * K * 3.03125, lambda: jet.quant_act(m["x"], out=m["qx"]))
-            timed(ge, fl, lambda: jet.fp8_linear_fwd(m["qx"]["q_row"], m["qx"]["s_row"], m["qw"][0], m["qw"][1], out=m["y"]))
+            timed(ge, fl, lambda: jet.fp8_linear_fwd(m["qx"]["q_row"], m["qx"]["s_row"], m["qw"][0], m["qw"][1], out=m["y"]), (m["name"], "fwd"))
             timed(qe, M * N * 4.0625, lambda: jet.quant_act(m["dy"], row=True, col=True, out=m["qdy"]))
-            timed(ge, fl, lambda: jet.fp8_linear_dgrad(m["qdy"]["q_row"], m["qdy"]["s_row"], m["qw"][2], m["qw"][3], out=m["dx"]))
+            timed(ge, fl, lambda: jet.fp8_linear_dgrad(m["qdy"]["q_row"], m["qdy"]["s_row"], m["qw"][2], m["qw"][3], out=m["dx"]), (m["name"], "dgrad"))
             timed(qe, M * K * 2.0625, lambda: jet.quant_act(m["qx"]["q_row"], m["qx"]["s_row"], row=False, col=True, out=m["qxT"]))
-            timed(we, fl, lambda: jet.fp8_linear_wgrad(m["qdy"]["q_colT"], m["qdy"]["s_colT"], m["qxT"]["q_colT"], m["qxT"]["s_colT"], out=m["dw"]))
+            timed(we, fl, lambda: jet.fp8_linear_wgrad(m["qdy"]["q_colT"], m["qdy"]["s_colT"], m["qxT"]["q_colT"], m["qxT"]["s_colT"], out=m["dw"]), (m["name"], "wgrad"))
             for d in m["dec"]:
                 jet.quant_act(d["x"], out=d["q"])
                 jet.fp8_linear_fwd(d["q"]["q_row"], d["q"]["s_row"], m["qw"][0], m["qw"][1], out=d["y"])
@@ -284,6 +288,11 @@ def main():
                      "algorithmic_bytes": round(tile_alg_bytes)},
     }
 
+    shape = {name: (N, K) for name, N, K in layer}
+    out["per_matrix_tflops"] = {}
+    for (name, kind), evs in per_matrix.items():
+        t = sum(a.elapsed_time(b) for a, b in evs) * 1e-3 / len(evs)
+        out["per_matrix_tflops"].setdefault(name, {})[kind] = round(2 * M * shape[name][0] * shape[name][1] / t / 1e12, 1)
     out["roofline"].update(sustained_mfma(torch, jet, g_rate))
     if not args.no_extras:
         out["requantize_8B_layer"] = requant_timing(torch, jet, mats)
@@ -298,6 +307,7 @@ def main():
     if not args.no_decode_sweep:
         out["decode"] = decode_sweep(torch, jet, layer)
         out["decode_32B"] = decode_sweep_32b(torch, jet)
+        out["decode_per_matrix_8B"] = decode_per_matrix(torch, jet, layer + FUSED_8B[:1] + FUSED_8B[2:3])
         d1 = out["decode"]["M=1"]
         out["roofline_decode"] = {"bound": "hbm", "kernel": "gemm_skinny_kernel (rollout FProp, M = 1, one 8B-class layer, "
                                   "weights streamed from HBM; q/k/v and gate/up each as one call)",
@@ -589,6 +599,51 @@ def decode_sweep(torch, jet, layer, rotations=4):
         res[k]["fused_us_per_layer"] = v["us_per_layer"]
         res[k]["fused_GB/s"] = v["GB/s"]
         res[k]["fused_frac_hbm"] = v["frac_hbm"]
+    return res
+
+
+def decode_per_matrix(torch, jet, layer, ms=(1, 32, 128)):
+    """Each matrix of the layer by itself, decode-shaped, against so many distinct copies of it (> 600 MB)
+    that every weight byte comes from HBM; one HIP graph per (matrix, M).  us per call and GB/s."""
+    dev = "cuda:0"
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(777)
+    res = {}
+    for name, N, K in layer:
+        copies = max(3, int(600e6 // (N * K)) + 1)
+        ws = [jet.quant_weight((torch.randn((N, K), generator=gen, device=dev) * 0.02).to(torch.bfloat16))
+              for _ in range(copies)]
+        res[name] = {}
+        for Md in ms:
+            a = jet.quant_act(torch.randn((Md, K), generator=gen, device=dev).to(torch.bfloat16))
+            y = torch.empty((Md, N), dtype=torch.bfloat16, device=dev)
+
+            def run():
+                for q, sc in ws:
+                    jet.fp8_linear_fwd(a["q_row"], a["s_row"], q, sc, out=y)
+
+            st = torch.cuda.Stream()
+            st.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(st):
+                run()
+            torch.cuda.current_stream().wait_stream(st)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                run()
+            g.replay()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            t = e0.elapsed_time(e1) * 1e-3 / (10 * copies)
+            by = N * K + 4 * (N // 128) * (K // 128) + Md * K + 4 * Md * (K // 128) + 2 * Md * N
+            res[name][f"M={Md}"] = {"us": round(t * 1e6, 2), "GB/s": round(by / t / 1e9)}
+        del ws
+        torch.cuda.empty_cache()
     return res
 
 
