@@ -1,11 +1,12 @@
-"""The library under HIP graph capture: every entry point only enqueues kernels on the caller's
-stream (no allocation, no synchronisation, no memset), so a captured sequence must replay to the
-bytes of the eager run, on every replay, also with other work and synchronisations in between."""
+"""The entry points under HIP graph capture and on a stream of the caller's: the library neither
+allocates nor synchronises (include/jet.h), so a captured sequence of calls must replay to the
+same bytes as the eager calls, replay after replay, with the program's own eager work and
+synchronisations in between."""
 import pytest
 import torch
 
 import jet_inputs as ji
-from jet_testlib import DEV, dev_bf16
+from jet_testlib import dev_bf16
 
 pytestmark = pytest.mark.gpu
 
@@ -18,75 +19,74 @@ def jet():
     return j
 
 
-def test_a_captured_layer_step_replays_to_the_eager_bytes(jet):
-    M, N, K = 384, 512, 1024
-    x = dev_bf16(ji.activations(M, K, seed=61))
-    w = dev_bf16(ji.weights(N, K, seed=62))
-    dy = dev_bf16(ji.grads(M, N, seed=63))
-    gamma = dev_bf16(ji.norm_weight(K, seed=64).reshape(1, K)).reshape(K)
-    gu = dev_bf16(ji.mlp_intermediate(M, K, seed=65))
+def _bits(t):
+    return t.contiguous().view(torch.int16)
 
-    bufs = {
-        "qx": jet.quant_act(x), "qw": jet.quant_weight(w, transposed=True),
-        "qdy": jet.quant_act(dy, row=True, col=True),
-        "y": torch.empty((M, N), dtype=torch.bfloat16, device=DEV),
-        "y1": torch.empty((1, N), dtype=torch.bfloat16, device=DEV),
-        "y40": torch.empty((40, N), dtype=torch.bfloat16, device=DEV),
-        "dx": torch.empty((M, K), dtype=torch.bfloat16, device=DEV),
-        "dw": torch.empty((N, K), dtype=torch.bfloat16, device=DEV),
-    }
-    bufs["qxT"] = jet.quant_act(bufs["qx"]["q_row"], bufs["qx"]["s_row"], row=False, col=True)
-    bufs["rn"] = jet.rmsnorm_quant(x, gamma, 1e-6)
-    bufs["sm"] = jet.silu_mul_quant(gu[:, :K], gu[:, K:])
 
-    def step():
-        b = bufs
-        jet.quant_act(x, out=b["qx"])
-        jet.quant_weight(w, transposed=True, out=b["qw"])
-        jet.quant_act(dy, row=True, col=True, out=b["qdy"])
-        jet.quant_act(b["qx"]["q_row"], b["qx"]["s_row"], row=False, col=True, out=b["qxT"])
-        jet.rmsnorm_quant(x, gamma, 1e-6, out=b["rn"])
-        jet.silu_mul_quant(gu[:, :K], gu[:, K:], out=b["sm"])
-        jet.fp8_linear_fwd(b["qx"]["q_row"], b["qx"]["s_row"], b["qw"][0], b["qw"][1], out=b["y"])      # tile kernel
-        jet.fp8_linear_fwd(b["qx"]["q_row"][:1], b["qx"]["s_row"][:1], b["qw"][0], b["qw"][1], out=b["y1"])   # skinny
-        jet.fp8_linear_fwd(b["qx"]["q_row"][:40], b["qx"]["s_row"][:40], b["qw"][0], b["qw"][1], out=b["y40"])  # strip
-        jet.fp8_linear_dgrad(b["qdy"]["q_row"], b["qdy"]["s_row"], b["qw"][2], b["qw"][3], out=b["dx"])
-        jet.fp8_linear_wgrad(b["qdy"]["q_colT"], b["qdy"]["s_colT"], b["qxT"]["q_colT"], b["qxT"]["s_colT"], out=b["dw"])
+def test_mlp_block_forward_and_backward_replayed_from_a_graph(jet):
+    from paper_2601_14243_amd import mlp_block
+    M, H, I = 256, 512, 1024
+    w = mlp_block.MlpWeights(dev_bf16(ji.weights(2 * I, H, 11)), dev_bf16(ji.weights(H, I, 12)))
+    inputs = [(dev_bf16(ji.activations(M, H, 20 + i)), dev_bf16(ji.grads(M, H, 30 + i))) for i in range(3)]
+    x, dy = inputs[0][0].clone(), inputs[0][1].clone()
 
-    def tensors():
-        b = bufs
-        return [b["qx"]["q_row"], b["qx"]["s_row"], *b["qw"], b["qdy"]["q_row"], b["qdy"]["s_row"],
-                b["qdy"]["q_colT"], b["qdy"]["s_colT"], b["qxT"]["q_colT"], b["qxT"]["s_colT"],
-                b["rn"]["q_row"], b["rn"]["s_row"], b["sm"]["q_row"], b["sm"]["s_row"],
-                b["y"], b["y1"], b["y40"], b["dx"], b["dw"]]
+    def run():
+        y, saved = mlp_block.forward(x, w)
+        g = mlp_block.backward(saved, dy, w)
+        return y, g["dx"], g["dw_gu"], g["dw_d"]
 
-    def snapshot():
-        torch.cuda.synchronize()
-        return [t.clone().view(torch.uint8) for t in tensors()]
-
-    def scrub():
-        for t in tensors():
-            t.view(torch.uint8).fill_(0xA5)
-
-    step()
-    eager = snapshot()
-
-    s = torch.cuda.Stream()
-    s.wait_stream(torch.cuda.current_stream())
-    with torch.cuda.stream(s):
-        step()
-    torch.cuda.current_stream().wait_stream(s)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                       # warm-up on the capture stream
+        run()
+    torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
-    g = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(g):
-        step()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        outs = run()
+    for rep in range(6):
+        xi, dyi = inputs[rep % 3]
+        x.copy_(xi)
+        dy.copy_(dyi)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [o.clone() for o in outs]
+        want = run()                                    # the program's own eager work between the replays
+        torch.cuda.synchronize()
+        for name, a, b in zip(("y", "dx", "dw_gu", "dw_d"), got, want):
+            assert torch.equal(_bits(a), _bits(b)), f"replay {rep}: {name} differs from the eager call"
 
-    for replay in range(4):
-        scrub()
-        if replay % 2:                       # eager work of the program between replays
-            torch.cuda.synchronize()
-            _ = (x.float() * 2).sum().item()
-        g.replay()
-        got = snapshot()
-        for i, (a, b) in enumerate(zip(got, eager)):
-            assert torch.equal(a, b), f"replay {replay}: tensor {i} differs from the eager run"
+
+def test_decode_calls_on_a_side_stream_and_in_a_graph(jet):
+    N, K = 1024, 2048
+    qw, sw = jet.quant_weight(dev_bf16(ji.weights(N, K, 41)))
+    xs = [dev_bf16(ji.activations(Md, K, 50 + Md)) for Md in (1, 5, 27, 100)]
+    eager = []
+    for xd in xs:
+        a = jet.quant_act(xd)
+        eager.append(jet.fp8_linear_fwd(a["q_row"], a["s_row"], qw, sw))
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        on_side = []
+        for xd in xs:
+            a = jet.quant_act(xd)
+            on_side.append(jet.fp8_linear_fwd(a["q_row"], a["s_row"], qw, sw))
+    side.synchronize()
+    for e, s in zip(eager, on_side):
+        assert torch.equal(_bits(e), _bits(s))
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        captured = []
+        for xd in xs:
+            a = jet.quant_act(xd)
+            captured.append(jet.fp8_linear_fwd(a["q_row"], a["s_row"], qw, sw))
+    for rep in range(3):
+        for c in captured:
+            c.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for e, c in zip(eager, captured):
+            assert torch.equal(_bits(e), _bits(c)), f"replay {rep}"
