@@ -60,6 +60,10 @@ def test_forward_shapes(jet, M, N, K):
 
 
 @pytest.mark.parametrize("M,N,K,kernel", [
+    (1, 4224, 384, "skinny kernel, two workgroups per CU (more than 256 strips), three groups"),
+    (5, 4224, 128, "skinny kernel, two workgroups per CU, one group: only the first wave has a unit"),
+    (8, 4224, 1152, "skinny kernel, two workgroups per CU, nine groups"),
+    (9, 4224, 384, "skinny kernel, two workgroups per CU, two activation blocks"),
     (20, 2048, 640, "skinny kernel, two row tiles, the second one 4 rows: three activation blocks copied"),
     (27, 2048, 640, "skinny kernel, two row tiles, the second one 11 rows: four activation blocks copied"),
     (27, 4608, 384, "strip kernel, one 32-row block (17-32 rows against more than 256 strips of 16 columns)"),
